@@ -1,0 +1,214 @@
+/*
+ * libcbm -- Compressed Binary Matrix (CBM) products on one AMD MI355X (gfx950).
+ *
+ * C ABI.  A binary m x n matrix A, given as CSR without values (each row a
+ * sorted list of column indices: the paper's adjacency-list input, Section 2),
+ * is compressed once into a CBM handle; the handle then multiplies any number
+ * of dense fp32 matrices (the "compressed once, multiplied many times" use of
+ * Section 1.2).  All dense operands are row-major fp32 in DEVICE memory; all
+ * index arrays passed to cbm_build are in HOST memory.
+ *
+ * Every function returns a cbm_status; nothing throws or aborts across this
+ * boundary, and output arguments are left untouched on failure.
+ */
+#ifndef CBM_H
+#define CBM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cbm_handle cbm_handle; /* opaque; owns its host and device arrays */
+
+typedef enum {
+    CBM_OK = 0,
+    CBM_ERR_INVALID_ARG = 1, /* null pointer, k <= 0, ld < k, bad option value      */
+    CBM_ERR_INVALID_CSR = 2, /* row offsets not monotone, columns unsorted, repeated
+                                or out of [0, n)                                     */
+    CBM_ERR_ALLOC = 3,       /* host or device allocation failed                     */
+    CBM_ERR_HIP = 4,         /* a HIP runtime call failed                            */
+    CBM_ERR_UNSUPPORTED = 5, /* size beyond what the index types can hold            */
+    CBM_ERR_STATE = 6        /* handle cannot do this (host-only handle, normalised
+                                product on a handle built without self-loops, ...)   */
+} cbm_status;
+
+/* cbm_build_opts.flags */
+#define CBM_FLAG_HOST_ONLY 1u /* build the format but upload nothing to a GPU:
+                                 cbm_stats / cbm_get_tree / cbm_decompress work,
+                                 products return CBM_ERR_STATE                      */
+
+/*
+ * Build options.  A NULL pointer means all zeros, i.e. the defaults below.
+ *
+ * alpha          Edge-pruning threshold of Section 2.2 ("Edge Pruning"): row x may
+ *                be compressed against row y only if that saves at least alpha
+ *                scalar operations, w(y,x) <= nnz(a_x) - alpha.  alpha = 0 keeps
+ *                every compression that strictly beats storing the row in full
+ *                (draws go to the virtual vertex, Section 2.2 after Eq. (5)).
+ * add_self_loops Compress A v I instead of A (needs m == n).  Required by
+ *                cbm_spmm_normalized, whose matrix is D^-1/2 (A + I) D^-1/2.
+ * max_depth      Cap on the depth of the compression tree (a row stored in full
+ *                has depth 1).  0 = library default (16); -1 = unlimited.  Each
+ *                level is one dependent kernel launch, so this is the knob that
+ *                trades compression for GPU parallelism.  Any cap yields a valid
+ *                CBM (exact product).
+ * hub_cap        Candidate search: columns with more than hub_cap entries are
+ *                not expanded when counting shared columns (their rows are still
+ *                compared exactly once they are candidates).  0 = default (512);
+ *                -1 = expand everything (exact shared-column search).
+ * max_candidates Candidate parents kept per row.  0 = default (8); -1 = keep all
+ *                (with hub_cap = -1, max_depth = -1 and alpha = 0 the tree is then
+ *                a true minimum spanning tree of the extended distance graph).
+ * num_threads    Host threads for the build.  0 = all hardware threads.
+ * device         HIP device that will own the arrays.  -1 = current device.
+ */
+typedef struct {
+    int32_t alpha;
+    int32_t add_self_loops;
+    int32_t max_depth;
+    int32_t hub_cap;
+    int32_t max_candidates;
+    int32_t num_threads;
+    int32_t device;
+    uint32_t flags;
+} cbm_build_opts;
+
+typedef struct {
+    int64_t m, n;
+    int64_t nnz;             /* nonzeros of the compressed matrix (A, or A v I)      */
+    int64_t num_delta_plus;  /* sum over rows of |Delta+|                            */
+    int64_t num_delta_minus; /* sum over rows of |Delta-|                            */
+    int64_t num_roots;       /* rows compressed against the virtual null row         */
+    int64_t num_internal;    /* rows that some other row is compressed against       */
+    int64_t scalar_ops;      /* Section 2.2: nnz(a_x) for a root, 1+|D+|+|D-| else   */
+    int64_t num_tasks;       /* GPU work items (rows, plus segments of split rows)   */
+    int64_t num_split_rows;  /* rows whose delta list is cut into several segments   */
+    int64_t bytes_csr;       /* int64 row offsets + int32 columns, no values         */
+    int64_t bytes_cbm;       /* packed device arrays of this handle                  */
+    int32_t depth;           /* number of tree levels = dependent launches           */
+    int32_t alpha;
+    int32_t add_self_loops;
+    int32_t reserved;
+    double build_seconds;
+} cbm_stats_t;
+
+/*
+ * cbm_build -- compress a binary CSR matrix (Section 2).
+ *   m, n      matrix shape; m, n >= 0, n < 2^31, m < 2^31.
+ *   rowptr    host, m + 1 entries, rowptr[0] = 0, non-decreasing.
+ *   colidx    host, rowptr[m] entries; within a row strictly increasing, in [0, n).
+ *   opts      host, or NULL for defaults.
+ *   out       receives the handle.
+ * The CSR arrays are only read during the call (copied, not retained).
+ * Builder = extended distance graph restricted to row pairs that share a column
+ * (only those can beat the virtual edge), Prim growth from the virtual vertex
+ * with the draw rule and the alpha rule, delta lists by list merge (Eq. (2)).
+ */
+cbm_status cbm_build(int64_t m, int64_t n, const int64_t* rowptr, const int32_t* colidx,
+                     const cbm_build_opts* opts, cbm_handle** out);
+
+/*
+ * cbm_spmm -- Y = A . X  (Eq. (5), Algorithm 1).
+ *   X   device, n x k row-major fp32, leading dimension ldx >= k (in floats).
+ *   Y   device, m x k row-major fp32, leading dimension ldy >= k.  Fully
+ *       overwritten (it need not be zeroed) and must not overlap X.  The tree
+ *       update runs in place in Y (Property 3).
+ *   hip_stream  a hipStream_t (NULL = default stream).  The call only enqueues
+ *       kernels and returns; the caller synchronises.
+ * If the handle was built with add_self_loops the product is (A v I) . X.
+ * k not a multiple of 4, or pointers / leading dimensions that are not 16-byte
+ * multiples, select a narrower-load variant of the same kernel, not an error.
+ * Not thread-safe per handle (rows with very long delta lists use scratch owned
+ * by the handle, sized on first use for a given k).
+ */
+cbm_status cbm_spmm(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
+                    void* hip_stream);
+
+/*
+ * cbm_spmm_normalized -- Y = D^-1/2 (A + I) D^-1/2 . X  (Eq. (1); Section 2.2,
+ * "Extending SpMM with CBM to normalized adjacency matrices"), D = row sums of
+ * A v I.  Same arguments as cbm_spmm.  Needs a square handle built with
+ * add_self_loops, else CBM_ERR_STATE.  The column scale d_j^-1/2 is applied to
+ * each gathered row of X, the row scale d_x^-1/2 when a row is written.
+ */
+cbm_status cbm_spmm_normalized(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y,
+                               int64_t ldy, void* hip_stream);
+
+/* Same as cbm_spmm_normalized followed by an element-wise max(., 0): the
+ * sigma(A_hat . Z) step of Eq. (1) with sigma = ReLU, fused into the row write. */
+cbm_status cbm_spmm_normalized_relu(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y,
+                                    int64_t ldy, void* hip_stream);
+
+/*
+ * cbm_dense_matmul -- C = A . B for dense row-major fp32 device matrices
+ * (the X . W products of Eq. (1)); fp32 MFMA, fp32 accumulation.
+ *   A  M x K (lda >= K),  B  K x N (ldb >= N),  C  M x N (ldc >= N), no overlap.
+ */
+cbm_status cbm_dense_matmul(int64_t M, int32_t N, int32_t K, const float* A, int64_t lda, const float* B,
+                            int64_t ldb, float* C, int64_t ldc, void* hip_stream);
+
+/*
+ * cbm_gcn2_forward -- two-layer GCN inference, Eq. (1):
+ *   out = A_hat . relu(A_hat . (X . W0)) . W1
+ * evaluated as Z0 = X W0, H = relu(A_hat Z0), Z1 = H W1, out = A_hat Z1.
+ *   X n x f_in, W0 f_in x hidden, W1 hidden x f_out, out n x f_out: device,
+ *   row-major, densely packed (leading dimension = number of columns).
+ *   workspace  device scratch of at least cbm_gcn2_workspace_bytes() bytes,
+ *              caller-owned, 16-byte aligned.
+ */
+cbm_status cbm_gcn2_forward(const cbm_handle* h, const float* X, int32_t f_in, const float* W0, int32_t hidden,
+                            const float* W1, int32_t f_out, float* out, void* workspace, size_t workspace_bytes,
+                            void* hip_stream);
+size_t cbm_gcn2_workspace_bytes(const cbm_handle* h, int32_t f_in, int32_t hidden, int32_t f_out);
+
+/* Counters of the built format (Properties 1 and 2, Lemma 2.2). */
+cbm_status cbm_stats(const cbm_handle* h, cbm_stats_t* out);
+
+/*
+ * cbm_get_tree -- the chain of compression, host arrays of m entries each (any
+ * may be NULL): parent[x] = row that x is compressed against, -1 for the virtual
+ * null row; nplus / nminus = |Delta+|, |Delta-| of the edge (parent[x], x);
+ * level[x] = depth of x, 1 for rows stored in full.
+ */
+cbm_status cbm_get_tree(const cbm_handle* h, int32_t* parent, int32_t* nplus, int32_t* nminus, int32_t* level);
+
+/*
+ * cbm_decompress -- rebuild the compressed matrix from the tree and the delta
+ * lists alone, a_x = (a_y u Delta+) \ Delta- (Eq. (2)).  Host outputs: rowptr
+ * (m + 1) and colidx (stats.nnz entries, sorted within rows).  Returns A v I
+ * when the handle was built with add_self_loops.
+ */
+cbm_status cbm_decompress(const cbm_handle* h, int64_t* rowptr, int32_t* colidx);
+
+/*
+ * Per-launch timing of the product kernels.  With profiling on, every kernel a
+ * product call enqueues is bracketed by HIP events on the caller's stream.
+ * After synchronising the stream, cbm_profile_read returns, for the most
+ * recent product call, up to `cap` records and the total count in *count.
+ */
+typedef struct {
+    int32_t kind;           /* 0 = gather/update level, 1 = segment pass, 2 = split-row
+                               combine, 3 = row-scale fix-up, 4 = dense matmul          */
+    int32_t level;          /* tree level for kinds 0 and 2, else 0                    */
+    int64_t tasks;          /* work items in the launch                               */
+    int64_t deltas;         /* delta entries gathered by the launch                   */
+    int64_t algorithmic_bytes; /* bytes the method itself must move in this launch    */
+    float milliseconds;
+    float reserved;
+} cbm_launch_record;
+cbm_status cbm_profile_enable(cbm_handle* h, int32_t on);
+cbm_status cbm_profile_read(cbm_handle* h, cbm_launch_record* records, int32_t cap, int32_t* count);
+
+void cbm_free(cbm_handle* h); /* NULL-safe; releases everything the handle owns */
+const char* cbm_status_string(cbm_status s);
+/* Text naming the HIP call and runtime error behind the calling thread's most recent
+ * CBM_ERR_HIP / CBM_ERR_ALLOC ("" if none).  Valid until that thread's next failing call. */
+const char* cbm_last_error_detail(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CBM_H */

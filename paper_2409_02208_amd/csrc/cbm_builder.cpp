@@ -1,0 +1,494 @@
+// Host-side CBM builder: binary CSR -> compression tree -> delta lists -> GPU work lists.
+//
+// Follows Section 2 of the paper (extended Hamming-distance graph with a virtual
+// null row, spanning tree rooted at the virtual vertex, delta lists per tree
+// edge, Eq. (2)) and the alpha rule of Section 2.2 ("Edge Pruning"), but never
+// materialises the all-pairs distance graph: an edge (y,x) can beat the virtual
+// edge of x only if  w(y,x) = nnz(a_x) + nnz(a_y) - 2|a_x n a_y| < nnz(a_x),
+// i.e. |a_x n a_y| > nnz(a_y)/2, so only rows sharing a column are candidates.
+// The tree is grown Prim-style from the virtual vertex with a cap on depth,
+// because each tree level is one dependent kernel launch on the GPU.
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <cmath>
+#include <cstring>
+#include <functional>
+#include <queue>
+#include <thread>
+
+#include "cbm_internal.h"
+
+namespace {
+
+constexpr int32_t kDefaultMaxDepth = 16;
+constexpr int32_t kDefaultHubCap = 512;
+constexpr int32_t kDefaultMaxCand = 8;
+constexpr int32_t kSplitLen = 512;  // delta entries per segment of a split row
+
+template <class F>
+void parallel_chunks(int nthreads, int64_t total, int64_t chunk, F&& fn) {
+    if (total <= 0) return;
+    std::atomic<int64_t> next{0};
+    auto worker = [&](int tid) {
+        for (;;) {
+            int64_t b = next.fetch_add(chunk);
+            if (b >= total) break;
+            fn(b, std::min(total, b + chunk), tid);
+        }
+    };
+    int nt = (int)std::max<int64_t>(1, std::min<int64_t>(nthreads, (total + chunk - 1) / chunk));
+    if (nt == 1) {
+        worker(0);
+        return;
+    }
+    std::vector<std::thread> pool;
+    pool.reserve(nt);
+    for (int t = 0; t < nt; ++t) pool.emplace_back(worker, t);
+    for (auto& th : pool) th.join();
+}
+
+// |a n b| for two sorted lists; binary search when one is much longer.
+int64_t intersect_size(const int32_t* a, int64_t na, const int32_t* b, int64_t nb) {
+    if (na > nb) {
+        std::swap(a, b);
+        std::swap(na, nb);
+    }
+    if (na == 0) return 0;
+    int64_t c = 0;
+    if (nb > 32 * na) {
+        const int32_t* lo = b;
+        const int32_t* end = b + nb;
+        for (int64_t i = 0; i < na; ++i) {
+            lo = std::lower_bound(lo, end, a[i]);
+            if (lo == end) break;
+            if (*lo == a[i]) ++c;
+        }
+        return c;
+    }
+    int64_t i = 0, j = 0;
+    while (i < na && j < nb) {
+        int32_t x = a[i], y = b[j];
+        c += (x == y);
+        i += (x <= y);
+        j += (y <= x);
+    }
+    return c;
+}
+
+struct Cand {
+    int32_t child, parent, w;
+};
+
+struct HeapEdge {
+    uint64_t key;  // (w << 1) | non-virtual : draws go to the virtual edge (Section 2.2)
+    int32_t x, y;  // y = -1: virtual
+    bool operator>(const HeapEdge& o) const {
+        if (key != o.key) return key > o.key;
+        if (x != o.x) return x > o.x;
+        return y > o.y;
+    }
+};
+
+}  // namespace
+
+cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const int32_t* in_colidx, cbm_handle* h) {
+    auto t0 = std::chrono::steady_clock::now();
+    const cbm_build_opts& o = h->opts;
+    if (o.alpha < 0 || o.max_depth < -1 || o.hub_cap < -1 || o.max_candidates < -1 || o.num_threads < 0)
+        return CBM_ERR_INVALID_ARG;
+    if (m >= INT32_MAX || n >= INT32_MAX) return CBM_ERR_UNSUPPORTED;
+    if (o.add_self_loops && m != n) return CBM_ERR_INVALID_ARG;
+    int nthreads = o.num_threads > 0 ? o.num_threads : (int)std::max(1u, std::thread::hardware_concurrency());
+    const int32_t alpha = o.alpha;
+    const int32_t min_saving = std::max(alpha, 1);  // strict gain at alpha = 0: draws go to the virtual edge
+    const int32_t max_depth = o.max_depth == 0 ? kDefaultMaxDepth : o.max_depth;  // -1 = unlimited
+    const int32_t hub_cap = o.hub_cap == 0 ? kDefaultHubCap : o.hub_cap;
+    const int32_t max_cand = o.max_candidates == 0 ? kDefaultMaxCand : o.max_candidates;
+    h->m = m;
+    h->n = n;
+    h->eff_alpha = alpha;
+    h->eff_max_depth = max_depth;
+    h->eff_hub_cap = hub_cap;
+    h->eff_max_cand = max_cand;
+    h->square_self_loops = o.add_self_loops != 0;
+
+    // ---- validate -------------------------------------------------------------------
+    if (in_rowptr[0] != 0) return CBM_ERR_INVALID_CSR;
+    for (int64_t i = 0; i < m; ++i)
+        if (in_rowptr[i + 1] < in_rowptr[i]) return CBM_ERR_INVALID_CSR;
+    {
+        std::atomic<bool> bad{false};
+        parallel_chunks(nthreads, m, 4096, [&](int64_t b, int64_t e, int) {
+            for (int64_t i = b; i < e; ++i) {
+                int64_t prev = -1;
+                for (int64_t p = in_rowptr[i]; p < in_rowptr[i + 1]; ++p) {
+                    int64_t c = in_colidx[p];
+                    if (c <= prev || c >= n) {
+                        bad = true;
+                        return;
+                    }
+                    prev = c;
+                }
+            }
+        });
+        if (bad) return CBM_ERR_INVALID_CSR;
+    }
+
+    // ---- the matrix that is compressed: A, or A v I ------------------------------------
+    std::vector<int64_t> own_rowptr;
+    std::vector<int32_t> own_colidx;
+    const int64_t* rowptr = in_rowptr;
+    const int32_t* colidx = in_colidx;
+    if (o.add_self_loops) {
+        own_rowptr.assign(m + 1, 0);
+        for (int64_t i = 0; i < m; ++i) {
+            const int32_t* b = in_colidx + in_rowptr[i];
+            const int32_t* e = in_colidx + in_rowptr[i + 1];
+            bool has = std::binary_search(b, e, (int32_t)i);
+            own_rowptr[i + 1] = own_rowptr[i] + (e - b) + (has ? 0 : 1);
+        }
+        own_colidx.resize(own_rowptr[m]);
+        parallel_chunks(nthreads, m, 4096, [&](int64_t b0, int64_t e0, int) {
+            for (int64_t i = b0; i < e0; ++i) {
+                const int32_t* b = in_colidx + in_rowptr[i];
+                const int32_t* e = in_colidx + in_rowptr[i + 1];
+                int32_t* out = own_colidx.data() + own_rowptr[i];
+                const int32_t* pos = std::lower_bound(b, e, (int32_t)i);
+                out = std::copy(b, pos, out);
+                if (pos == e || *pos != (int32_t)i) *out++ = (int32_t)i;
+                std::copy(pos, e, out);
+            }
+        });
+        rowptr = own_rowptr.data();
+        colidx = own_colidx.data();
+    }
+    const int64_t nnz = rowptr[m];
+    if (nnz >= (int64_t)UINT32_MAX) return CBM_ERR_UNSUPPORTED;
+    h->rownnz.resize(m);
+    for (int64_t i = 0; i < m; ++i) {
+        int64_t len = rowptr[i + 1] - rowptr[i];
+        h->rownnz[i] = (int32_t)len;
+    }
+    auto row = [&](int64_t i) { return colidx + rowptr[i]; };
+    auto rlen = [&](int64_t i) { return (int64_t)h->rownnz[i]; };
+
+    // ---- transpose: rows holding each column ------------------------------------------
+    std::vector<int64_t> tptr(n + 1, 0);
+    std::vector<int32_t> trow(nnz);
+    for (int64_t p = 0; p < nnz; ++p) ++tptr[colidx[p] + 1];
+    for (int64_t j = 0; j < n; ++j) tptr[j + 1] += tptr[j];
+    {
+        std::vector<int64_t> fill(tptr.begin(), tptr.end() - 1);
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) trow[fill[colidx[p]]++] = (int32_t)i;
+    }
+
+    // ---- candidate parents: rows sharing columns, ranked by exact Hamming distance ------
+    std::vector<std::vector<Cand>> cand_per_thread(nthreads);
+    {
+        std::vector<std::vector<int32_t>> counters(nthreads), touched(nthreads);
+        parallel_chunks(nthreads, m, 64, [&](int64_t b, int64_t e, int tid) {
+            auto& cnt = counters[tid];
+            auto& tch = touched[tid];
+            auto& out = cand_per_thread[tid];
+            if (cnt.empty()) cnt.assign(m, 0);
+            struct Scored {
+                int64_t score;  // saving = nnz(a_x) - w(y,x) = 2|a_x n a_y| - nnz(a_y) (upper bound, then exact)
+                int32_t y;
+            };
+            std::vector<Scored> sc;
+            for (int64_t x = b; x < e; ++x) {
+                const int64_t nx = rlen(x);
+                if (nx < 1) continue;
+                tch.clear();
+                int64_t nhub = 0;
+                for (const int32_t* pj = row(x); pj != row(x) + nx; ++pj) {
+                    int64_t deg = tptr[*pj + 1] - tptr[*pj];
+                    if (hub_cap >= 0 && deg > hub_cap) {
+                        ++nhub;
+                        continue;
+                    }
+                    for (int64_t q = tptr[*pj]; q < tptr[*pj + 1]; ++q) {
+                        int32_t y = trow[q];
+                        if (cnt[y]++ == 0) tch.push_back(y);
+                    }
+                }
+                sc.clear();
+                for (int32_t y : tch) {
+                    int64_t ipart = cnt[y];
+                    cnt[y] = 0;
+                    if (y == x) continue;
+                    int64_t ny = rlen(y);
+                    int64_t iub = ipart + std::min<int64_t>(nhub, std::min(ny, nx) - ipart);
+                    int64_t ub = 2 * iub - ny;
+                    if (ub >= min_saving) sc.push_back({ub, y});
+                }
+                if (sc.empty()) continue;
+                auto better = [](const Scored& a, const Scored& b2) {
+                    return a.score != b2.score ? a.score > b2.score : a.y < b2.y;
+                };
+                if (nhub > 0) {
+                    // shared hub columns were not counted: settle the best few by exact intersection
+                    size_t keep = max_cand < 0 ? sc.size() : std::min<size_t>(sc.size(), 2 * (size_t)max_cand);
+                    if (keep < sc.size()) {
+                        std::nth_element(sc.begin(), sc.begin() + keep, sc.end(), better);
+                        sc.resize(keep);
+                    }
+                    size_t w = 0;
+                    for (auto& s : sc) {
+                        int64_t ny = rlen(s.y);
+                        int64_t I = intersect_size(row(x), nx, row(s.y), ny);
+                        s.score = 2 * I - ny;
+                        if (s.score >= min_saving) sc[w++] = s;
+                    }
+                    sc.resize(w);
+                }
+                size_t keep = max_cand < 0 ? sc.size() : std::min<size_t>(sc.size(), (size_t)max_cand);
+                if (keep < sc.size()) {
+                    std::nth_element(sc.begin(), sc.begin() + keep, sc.end(), better);
+                    sc.resize(keep);
+                }
+                for (auto& s : sc) out.push_back({(int32_t)x, s.y, (int32_t)(nx - s.score)});
+            }
+        });
+    }
+
+    // bucket candidate edges by parent: Prim pushes the out-edges of each newly attached row
+    std::vector<int64_t> optr(m + 1, 0);
+    for (auto& v : cand_per_thread)
+        for (auto& c : v) ++optr[c.parent + 1];
+    for (int64_t i = 0; i < m; ++i) optr[i + 1] += optr[i];
+    std::vector<int32_t> ochild(optr[m]), ow(optr[m]);
+    {
+        std::vector<int64_t> fill(optr.begin(), optr.end() - 1);
+        for (auto& v : cand_per_thread) {
+            for (auto& c : v) {
+                int64_t p = fill[c.parent]++;
+                ochild[p] = c.child;
+                ow[p] = c.w;
+            }
+            std::vector<Cand>().swap(v);
+        }
+    }
+
+    // ---- tree: Prim growth from the virtual vertex, depth-capped -------------------------
+    h->parent.assign(m, -1);
+    h->level.assign(m, 0);
+    {
+        std::vector<HeapEdge> init;
+        init.reserve(m);
+        for (int64_t x = 0; x < m; ++x) init.push_back({(uint64_t)rlen(x) << 1, (int32_t)x, -1});
+        std::priority_queue<HeapEdge, std::vector<HeapEdge>, std::greater<HeapEdge>> pq(std::greater<HeapEdge>(),
+                                                                                        std::move(init));
+        while (!pq.empty()) {
+            HeapEdge e = pq.top();
+            pq.pop();
+            if (h->level[e.x] != 0) continue;
+            int32_t lvl = e.y < 0 ? 1 : h->level[e.y] + 1;
+            h->parent[e.x] = e.y;
+            h->level[e.x] = lvl;
+            if (max_depth > 0 && lvl >= max_depth) continue;  // nothing may hang below the cap
+            for (int64_t p = optr[e.x]; p < optr[e.x + 1]; ++p)
+                if (h->level[ochild[p]] == 0) pq.push({((uint64_t)ow[p] << 1) | 1u, ochild[p], e.x});
+        }
+    }
+    std::vector<int64_t>().swap(optr);
+    std::vector<int32_t>().swap(ochild);
+    std::vector<int32_t>().swap(ow);
+    std::vector<int64_t>().swap(tptr);
+    std::vector<int32_t>().swap(trow);
+
+    // ---- delta lists (Eq. (2)) by list merge ------------------------------------------------
+    h->nplus.assign(m, 0);
+    h->nminus.assign(m, 0);
+    parallel_chunks(nthreads, m, 1024, [&](int64_t b, int64_t e, int) {
+        for (int64_t x = b; x < e; ++x) {
+            int32_t y = h->parent[x];
+            if (y < 0) {
+                h->nplus[x] = (int32_t)rlen(x);
+                continue;
+            }
+            int64_t I = intersect_size(row(x), rlen(x), row(y), rlen(y));
+            h->nplus[x] = (int32_t)(rlen(x) - I);
+            h->nminus[x] = (int32_t)(rlen(y) - I);
+        }
+    });
+    h->dptr.assign(m + 1, 0);
+    for (int64_t x = 0; x < m; ++x) h->dptr[x + 1] = h->dptr[x] + h->nplus[x] + h->nminus[x];
+    const int64_t nd = h->dptr[m];
+    h->dcol.resize(nd);
+    parallel_chunks(nthreads, m, 1024, [&](int64_t b, int64_t e, int) {
+        for (int64_t x = b; x < e; ++x) {
+            uint32_t* plus = h->dcol.data() + h->dptr[x];
+            int32_t y = h->parent[x];
+            if (y < 0) {
+                for (int64_t i = 0; i < rlen(x); ++i) plus[i] = (uint32_t)row(x)[i];
+                continue;
+            }
+            uint32_t* minus = plus + h->nplus[x];
+            const int32_t *a = row(x), *ae = a + rlen(x), *c = row(y), *ce = c + rlen(y);
+            while (a != ae && c != ce) {
+                if (*a == *c) {
+                    ++a;
+                    ++c;
+                } else if (*a < *c) {
+                    *plus++ = (uint32_t)*a++;
+                } else {
+                    *minus++ = (uint32_t)*c++ | CBM_DELTA_MINUS;
+                }
+            }
+            while (a != ae) *plus++ = (uint32_t)*a++;
+            while (c != ce) *minus++ = (uint32_t)*c++ | CBM_DELTA_MINUS;
+        }
+    });
+
+    // ---- D^-1/2 of A v I ---------------------------------------------------------------------
+    if (h->square_self_loops) {
+        h->dinv.resize(m);
+        for (int64_t i = 0; i < m; ++i) h->dinv[i] = (float)(1.0 / std::sqrt((double)rlen(i)));
+    }
+
+    // ---- levels and GPU work lists -------------------------------------------------------------
+    int32_t depth = 0;
+    for (int64_t x = 0; x < m; ++x) depth = std::max(depth, h->level[x]);
+    std::vector<uint8_t> internal(m, 0);
+    for (int64_t x = 0; x < m; ++x)
+        if (h->parent[x] >= 0) internal[h->parent[x]] = 1;
+    for (int64_t x = 0; x < m; ++x)
+        if (internal[x]) h->internal_rows.push_back((int32_t)x);
+
+    std::vector<int64_t> lcount(depth + 1, 0);
+    for (int64_t x = 0; x < m; ++x) ++lcount[h->level[x]];
+    std::vector<std::vector<int32_t>> by_level(depth + 1);
+    for (int l = 1; l <= depth; ++l) by_level[l].reserve(lcount[l]);
+    for (int64_t x = 0; x < m; ++x) by_level[h->level[x]].push_back((int32_t)x);
+
+    h->levels.assign(depth, CbmLevel{});
+    h->tasks.clear();
+    h->comb.clear();
+    h->num_slots = 0;
+    int64_t split_rows = 0;
+    // segments of every split row go in front of level 1: they depend on nothing
+    std::vector<CbmTask> segs;
+    for (int l = 1; l <= depth; ++l) {
+        for (int32_t x : by_level[l]) {
+            int64_t len = h->dptr[x + 1] - h->dptr[x];
+            if (len <= kSplitLen) continue;
+            ++split_rows;
+            int64_t nseg = (len + kSplitLen - 1) / kSplitLen;
+            CbmTask c{x, h->parent[x], (uint32_t)h->num_slots, (uint32_t)nseg | (internal[x] ? CBM_TASK_INTERNAL : 0u)};
+            h->comb.push_back(c);  // regrouped by level below
+            for (int64_t s = 0; s < nseg; ++s) {
+                int64_t b = h->dptr[x] + s * kSplitLen;
+                int64_t e = std::min<int64_t>(h->dptr[x + 1], b + kSplitLen);
+                segs.push_back({(int32_t)(h->num_slots + s), -1, (uint32_t)b, (uint32_t)(e - b) | CBM_TASK_SEGMENT});
+            }
+            h->num_slots += nseg;
+        }
+    }
+    // comb[] was filled level by level already (outer loop over l), record the ranges
+    {
+        int64_t pos = 0;
+        for (int l = 1; l <= depth; ++l) {
+            CbmLevel& L = h->levels[l - 1];
+            L.comb_begin = pos;
+            while (pos < (int64_t)h->comb.size() && h->level[h->comb[pos].row] == l) {
+                L.comb_segments += h->comb[pos].len_flags & CBM_TASK_LEN_MASK;
+                L.comb_parent_reads += h->comb[pos].parent >= 0;
+                ++pos;
+            }
+            L.comb_count = pos - L.comb_begin;
+        }
+    }
+    for (int l = 1; l <= depth; ++l) {
+        CbmLevel& L = h->levels[l - 1];
+        L.task_begin = (int64_t)h->tasks.size();
+        std::vector<CbmTask> lt;
+        if (l == 1) {
+            lt = std::move(segs);
+            L.segments = (int64_t)lt.size();
+        }
+        for (int32_t x : by_level[l]) {
+            int64_t len = h->dptr[x + 1] - h->dptr[x];
+            if (len > kSplitLen) continue;
+            lt.push_back({x, h->parent[x], (uint32_t)h->dptr[x], (uint32_t)len | (internal[x] ? CBM_TASK_INTERNAL : 0u)});
+            ++L.rows_written;
+            L.parent_reads += h->parent[x] >= 0;
+        }
+        // longest first: wave-mates get similar lengths and the tail of the launch is short
+        std::stable_sort(lt.begin(), lt.end(), [](const CbmTask& a, const CbmTask& b2) {
+            return (a.len_flags & CBM_TASK_LEN_MASK) > (b2.len_flags & CBM_TASK_LEN_MASK);
+        });
+        for (auto& t : lt) L.deltas += t.len_flags & CBM_TASK_LEN_MASK;
+        L.task_count = (int64_t)lt.size();
+        h->tasks.insert(h->tasks.end(), lt.begin(), lt.end());
+    }
+
+    // ---- counters (Properties 1 and 2) -----------------------------------------------------------
+    cbm_stats_t& s = h->stats;
+    std::memset(&s, 0, sizeof(s));
+    s.m = m;
+    s.n = n;
+    s.nnz = nnz;
+    for (int64_t x = 0; x < m; ++x) {
+        s.num_delta_plus += h->nplus[x];
+        s.num_delta_minus += h->nminus[x];
+        if (h->parent[x] < 0) {
+            ++s.num_roots;
+            s.scalar_ops += rlen(x);
+        } else {
+            s.scalar_ops += 1 + h->nplus[x] + h->nminus[x];
+        }
+    }
+    s.num_internal = (int64_t)h->internal_rows.size();
+    s.num_tasks = (int64_t)h->tasks.size();
+    s.num_split_rows = split_rows;
+    s.bytes_csr = 8 * (m + 1) + 4 * in_rowptr[m];
+    s.bytes_cbm = 4 * nd + (int64_t)sizeof(CbmTask) * (int64_t)(h->tasks.size() + h->comb.size()) +
+                  4 * (int64_t)h->internal_rows.size() + 4 * (int64_t)h->dinv.size();
+    s.depth = depth;
+    s.alpha = alpha;
+    s.add_self_loops = o.add_self_loops != 0;
+    s.build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    return CBM_OK;
+}
+
+cbm_status cbm_decompress_host(const cbm_handle* h, int64_t* rowptr, int32_t* colidx) {
+    const int64_t m = h->m;
+    rowptr[0] = 0;
+    for (int64_t x = 0; x < m; ++x) rowptr[x + 1] = rowptr[x] + h->rownnz[x];
+    // parents before children: visit rows by level; a row is rebuilt from its parent's rebuilt
+    // list and its own two delta lists only (Eq. (2))
+    std::vector<int32_t> order(m);
+    for (int64_t x = 0; x < m; ++x) order[x] = (int32_t)x;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return h->level[a] < h->level[b]; });
+    for (int32_t x : order) {
+        const uint32_t* plus = h->dcol.data() + h->dptr[x];
+        const uint32_t* pe = plus + h->nplus[x];
+        const uint32_t* minus = pe;
+        const uint32_t* me = minus + h->nminus[x];
+        int32_t* out = colidx + rowptr[x];
+        int32_t* oe = colidx + rowptr[x + 1];
+        int32_t y = h->parent[x];
+        const int32_t* a = y >= 0 ? colidx + rowptr[y] : nullptr;
+        const int32_t* ae = y >= 0 ? colidx + rowptr[y + 1] : nullptr;
+        // (a_y \ Delta-) merged with Delta+
+        while (a != ae || plus != pe) {
+            if (a != ae && minus != me && (uint32_t)*a == (*minus & ~CBM_DELTA_MINUS)) {
+                ++a;
+                ++minus;
+                continue;
+            }
+            int32_t v;
+            if (plus == pe || (a != ae && (uint32_t)*a < *plus))
+                v = *a++;
+            else
+                v = (int32_t)*plus++;
+            if (out == oe) return CBM_ERR_STATE;
+            *out++ = v;
+        }
+        if (out != oe || minus != me) return CBM_ERR_STATE;
+    }
+    return CBM_OK;
+}

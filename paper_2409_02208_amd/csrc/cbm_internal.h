@@ -1,0 +1,91 @@
+// Internal layout shared by the host builder, the kernel launchers and the C ABI.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "cbm.h"
+
+// One GPU work item: gather `len` signed delta columns starting at dcol[start],
+// add the parent's finished row, write row `row`.
+//   parent  >= 0: row whose result is added first;  -1: none (virtual null row).
+//   len     low 24 bits = number of delta entries; high bits = CBM_TASK_* flags.
+// A delta entry is a column index with the sign in bit 31 (set = Delta-).
+struct CbmTask {
+    int32_t row;
+    int32_t parent;
+    uint32_t start;
+    uint32_t len_flags;
+};
+
+constexpr uint32_t CBM_TASK_LEN_MASK = 0x00ffffffu;
+constexpr uint32_t CBM_TASK_INTERNAL = 0x01000000u;  // some row is compressed against this one
+constexpr uint32_t CBM_TASK_SEGMENT = 0x02000000u;   // `row` is a scratch slot, not a matrix row
+constexpr uint32_t CBM_DELTA_MINUS = 0x80000000u;
+
+struct CbmLevel {
+    int64_t task_begin = 0, task_count = 0;        // into tasks[]: whole rows of this level (+ all segments, level 1)
+    int64_t comb_begin = 0, comb_count = 0;        // into comb[]: split rows of this level
+    int64_t deltas = 0;                            // delta entries gathered by the level's main launch
+    int64_t parent_reads = 0;                      // tasks in the main launch with a parent
+    int64_t rows_written = 0;                      // matrix rows written by the main launch
+    int64_t segments = 0;                          // segment tasks in the main launch
+    int64_t comb_segments = 0;                     // scratch rows read by the combine launch
+    int64_t comb_parent_reads = 0;
+};
+
+struct cbm_handle {
+    int64_t m = 0, n = 0;
+    cbm_build_opts opts{};
+    int32_t eff_alpha = 0, eff_max_depth = 0, eff_hub_cap = 0, eff_max_cand = 0;
+    bool square_self_loops = false;
+
+    // ---- host copy of the format -------------------------------------------------
+    std::vector<int32_t> rownnz;   // nnz of each compressed row (A or A v I)
+    std::vector<int32_t> parent;   // -1 = virtual null row
+    std::vector<int32_t> level;    // 1 = stored in full
+    std::vector<int32_t> nplus, nminus;
+    std::vector<int64_t> dptr;     // m + 1
+    std::vector<uint32_t> dcol;    // Delta+ then Delta- of each row, sign in bit 31
+    std::vector<float> dinv;       // d_x^-1/2 (square_self_loops only)
+    std::vector<CbmTask> tasks;
+    std::vector<CbmTask> comb;     // split rows: start = first scratch slot, len = number of segments
+    std::vector<int32_t> internal_rows;
+    std::vector<CbmLevel> levels;  // levels[0] is tree level 1
+    int64_t num_slots = 0;         // scratch rows needed by split rows
+    cbm_stats_t stats{};
+
+    // ---- device arrays (owned) ---------------------------------------------------
+    int device = -1;
+    bool on_device = false;
+    CbmTask* d_tasks = nullptr;
+    CbmTask* d_comb = nullptr;
+    uint32_t* d_dcol = nullptr;
+    float* d_dinv = nullptr;
+    int32_t* d_internal = nullptr;
+    mutable float* d_scratch = nullptr;  // num_slots x scratch_k floats, sized on first use
+    mutable int64_t scratch_k = 0;
+
+    // ---- per-launch profiling ----------------------------------------------------
+    bool profiling = false;
+    mutable std::vector<cbm_launch_record> prof_records;
+    mutable std::vector<void*> prof_events;  // hipEvent_t pairs
+};
+
+// Detail text of the most recent failure on this thread (which HIP call, which error).
+void cbm_set_error_detail(const char* what, const char* detail);
+const char* cbm_get_error_detail();
+
+// host builder (cbm_builder.cpp)
+cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* rowptr, const int32_t* colidx, cbm_handle* h);
+cbm_status cbm_decompress_host(const cbm_handle* h, int64_t* rowptr, int32_t* colidx);
+
+// device side (cbm_kernels.hip)
+enum CbmEpilogue { CBM_EPI_NONE = 0, CBM_EPI_ROWSCALE = 1, CBM_EPI_ROWSCALE_RELU = 2 };
+cbm_status cbm_upload(cbm_handle* h);
+void cbm_release_device(cbm_handle* h);
+cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
+                              CbmEpilogue epi, void* stream);
+// dense fp32 MFMA matmul (cbm_gemm.hip)
+cbm_status cbm_launch_gemm(int64_t M, int32_t N, int32_t K, const float* A, int64_t lda, const float* B, int64_t ldb,
+                           float* C, int64_t ldc, void* stream);

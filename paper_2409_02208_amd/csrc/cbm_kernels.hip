@@ -1,0 +1,391 @@
+// CBM product kernels for gfx950 (wave64) and their launch logic.
+//
+// One launch per tree level (Algorithm 1 visits tree edges in topological order;
+// rows of one level do not depend on each other).  A launch fuses the two stages
+// of Section 2.2: for each row x of the level
+//     Y[x,:] = Y[r_x,:] + sum_{j in Delta+} X[j,:] - sum_{j in Delta-} X[j,:]        (Eq. (5))
+// so a compressed row costs one parent-row read instead of a read-modify-write.
+// A group of LANES lanes owns one row and VEC consecutive columns per lane; a
+// wave carries 64/LANES rows.  Delta columns are fetched cooperatively (one
+// coalesced load per LANES entries) and broadcast inside the group.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+
+#include "cbm_internal.h"
+
+#define HIP_TRY(call, status)                                      \
+    do {                                                          \
+        hipError_t err_ = (call);                                 \
+        if (err_ != hipSuccess) {                                 \
+            cbm_set_error_detail(#call, hipGetErrorString(err_)); \
+            return (status);                                      \
+        }                                                         \
+    } while (0)
+
+namespace {
+
+template <int VEC>
+struct Vec;
+template <>
+struct Vec<1> {
+    float v[1];
+};
+template <>
+struct alignas(8) Vec<2> {
+    float v[2];
+};
+template <>
+struct alignas(16) Vec<4> {
+    float v[4];
+};
+
+template <int VEC>
+__device__ __forceinline__ Vec<VEC> ld(const float* p) {
+    return *reinterpret_cast<const Vec<VEC>*>(p);
+}
+template <int VEC>
+__device__ __forceinline__ void st(float* p, const Vec<VEC>& x) {
+    *reinterpret_cast<Vec<VEC>*>(p) = x;
+}
+
+// MODE 0: Y = A X.  MODE 1: Y = D^-1/2 (A v I) D^-1/2 X.  MODE 2: MODE 1 then max(., 0).
+// In MODE 1/2 a row that other rows are compressed against (CBM_TASK_INTERNAL) is
+// written unscaled, because its children add its unscaled sum (the row scale
+// belongs to the update step, Section 2.2); cbm_rowscale_kernel scales those rows
+// once every level is done.
+template <int VEC, int LANES, int MODE>
+__device__ __forceinline__ void write_row(const CbmTask& tk, Vec<VEC> acc, float* Y, int64_t ldy, float* scratch,
+                                          int64_t ld_scratch, const float* __restrict__ dinv, int c0) {
+    float* dst;
+    if (tk.len_flags & CBM_TASK_SEGMENT) {
+        dst = scratch + (int64_t)tk.row * ld_scratch + c0;
+    } else {
+        dst = Y + (int64_t)tk.row * ldy + c0;
+        if (MODE != 0 && !(tk.len_flags & CBM_TASK_INTERNAL)) {
+            const float s = dinv[tk.row];
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) {
+                acc.v[c] *= s;
+                if (MODE == 2) acc.v[c] = fmaxf(acc.v[c], 0.0f);
+            }
+        }
+    }
+    st<VEC>(dst, acc);
+}
+
+template <int VEC, int LANES, int MODE>
+__global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restrict__ tasks, int64_t ntasks,
+                                                        const uint32_t* __restrict__ dcol,
+                                                        const float* __restrict__ X, int64_t ldx, float* Y,
+                                                        int64_t ldy, float* scratch, int64_t ld_scratch,
+                                                        const float* __restrict__ dinv, int k) {
+    constexpr int G = 64 / LANES;               // rows per wave
+    constexpr int U = LANES < 8 ? LANES : 8;    // X rows in flight per group
+    const int lane = threadIdx.x & 63;
+    const int sub = lane / LANES;
+    const int sl = lane % LANES;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t t = wave * G + sub;
+    if (t >= ntasks) return;  // a whole group leaves together: no lane it exchanges with is gone
+    const CbmTask tk = tasks[t];
+    const uint32_t len = tk.len_flags & CBM_TASK_LEN_MASK;
+    const int c0 = (blockIdx.y * LANES + sl) * VEC;
+    const bool colok = c0 < k;
+
+    Vec<VEC> acc;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) acc.v[c] = 0.0f;
+    if (tk.parent >= 0 && colok) acc = ld<VEC>(Y + (int64_t)tk.parent * ldy + c0);
+
+    const uint32_t* dc = dcol + tk.start;
+    for (uint32_t i = 0; i < len; i += LANES) {
+        uint32_t e = 0;
+        float wgt = 0.0f;
+        if (i + sl < len) {
+            e = dc[i + sl];
+            if (MODE != 0) {
+                wgt = dinv[e & ~CBM_DELTA_MINUS];
+                wgt = (e & CBM_DELTA_MINUS) ? -wgt : wgt;
+            }
+        }
+        const int cnt = (int)min((uint32_t)LANES, len - i);
+        for (int u0 = 0; u0 < cnt; u0 += U) {
+            Vec<VEC> x[U];
+            uint32_t eu[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                eu[u] = (uint32_t)__shfl((int)e, u0 + u, LANES);
+                if (u0 + u < cnt && colok) {
+                    x[u] = ld<VEC>(X + (int64_t)(eu[u] & ~CBM_DELTA_MINUS) * ldx + c0);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) x[u].v[c] = 0.0f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (MODE != 0) {
+                    const float w = __shfl(wgt, u0 + u, LANES);
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(w, x[u].v[c], acc.v[c]);
+                } else {
+                    const uint32_t sgn = eu[u] & CBM_DELTA_MINUS;
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c)
+                        acc.v[c] += __uint_as_float(__float_as_uint(x[u].v[c]) ^ sgn);
+                }
+            }
+        }
+    }
+    if (colok) write_row<VEC, LANES, MODE>(tk, acc, Y, ldy, scratch, ld_scratch, dinv, c0);
+}
+
+// Rows whose delta list was cut into segments: Y[x,:] = Y[r_x,:] + sum of the row's segment sums.
+template <int VEC, int LANES, int MODE>
+__global__ __launch_bounds__(256) void cbm_combine_kernel(const CbmTask* __restrict__ comb, int64_t ncomb, float* Y,
+                                                          int64_t ldy, const float* scratch, int64_t ld_scratch,
+                                                          const float* __restrict__ dinv, int k) {
+    constexpr int G = 64 / LANES;
+    const int lane = threadIdx.x & 63;
+    const int64_t t = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * G + lane / LANES;
+    const int c0 = (blockIdx.y * LANES + lane % LANES) * VEC;
+    if (t >= ncomb || c0 >= k) return;
+    const CbmTask tk = comb[t];
+    const uint32_t nseg = tk.len_flags & CBM_TASK_LEN_MASK;
+    Vec<VEC> acc;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) acc.v[c] = 0.0f;
+    if (tk.parent >= 0) acc = ld<VEC>(Y + (int64_t)tk.parent * ldy + c0);
+    for (uint32_t s = 0; s < nseg; ++s) {
+        const Vec<VEC> p = ld<VEC>(scratch + (int64_t)(tk.start + s) * ld_scratch + c0);
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc.v[c] += p.v[c];
+    }
+    CbmTask out = tk;
+    out.len_flags &= ~CBM_TASK_SEGMENT;
+    write_row<VEC, LANES, MODE>(out, acc, Y, ldy, nullptr, 0, dinv, c0);
+}
+
+// Deferred row scale of the rows that have children (MODE 1/2 only).
+template <int MODE>
+__global__ __launch_bounds__(256) void cbm_rowscale_kernel(const int32_t* __restrict__ rows, int64_t nrows, float* Y,
+                                                           int64_t ldy, const float* __restrict__ dinv, int k) {
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= nrows) return;
+    const int32_t x = rows[r];
+    const float s = dinv[x];
+    float* y = Y + (int64_t)x * ldy;
+    for (int c = threadIdx.x & 63; c < k; c += 64) {
+        float v = y[c] * s;
+        if (MODE == 2) v = fmaxf(v, 0.0f);
+        y[c] = v;
+    }
+}
+
+struct LaunchCtx {
+    const cbm_handle* h;
+    const float* X;
+    int64_t ldx;
+    int k;
+    float* Y;
+    int64_t ldy;
+    int64_t ld_scratch;
+    hipStream_t stream;
+};
+
+template <int VEC, int LANES, int MODE>
+void launch_level(const LaunchCtx& c, const CbmLevel& L) {
+    constexpr int G = 64 / LANES;
+    const int ychunks = (c.k + LANES * VEC - 1) / (LANES * VEC);
+    if (L.task_count > 0) {
+        dim3 grid((unsigned)((L.task_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
+        hipLaunchKernelGGL((cbm_level_kernel<VEC, LANES, MODE>), grid, dim3(256), 0, c.stream,
+                           c.h->d_tasks + L.task_begin, L.task_count, c.h->d_dcol, c.X, c.ldx, c.Y, c.ldy,
+                           c.h->d_scratch, c.ld_scratch, c.h->d_dinv, c.k);
+    }
+}
+template <int VEC, int LANES, int MODE>
+void launch_combine(const LaunchCtx& c, const CbmLevel& L) {
+    constexpr int G = 64 / LANES;
+    const int ychunks = (c.k + LANES * VEC - 1) / (LANES * VEC);
+    dim3 grid((unsigned)((L.comb_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
+    hipLaunchKernelGGL((cbm_combine_kernel<VEC, LANES, MODE>), grid, dim3(256), 0, c.stream,
+                       c.h->d_comb + L.comb_begin, L.comb_count, c.Y, c.ldy, c.h->d_scratch, c.ld_scratch,
+                       c.h->d_dinv, c.k);
+}
+
+using LevelFn = void (*)(const LaunchCtx&, const CbmLevel&);
+struct Variant {
+    LevelFn level, combine;
+};
+
+template <int VEC, int LANES>
+Variant pick_mode(int mode) {
+    switch (mode) {
+        case 0: return {launch_level<VEC, LANES, 0>, launch_combine<VEC, LANES, 0>};
+        case 1: return {launch_level<VEC, LANES, 1>, launch_combine<VEC, LANES, 1>};
+        default: return {launch_level<VEC, LANES, 2>, launch_combine<VEC, LANES, 2>};
+    }
+}
+template <int VEC>
+Variant pick_lanes(int lanes, int mode) {
+    switch (lanes) {
+        case 4: return pick_mode<VEC, 4>(mode);
+        case 8: return pick_mode<VEC, 8>(mode);
+        case 16: return pick_mode<VEC, 16>(mode);
+        case 32: return pick_mode<VEC, 32>(mode);
+        default: return pick_mode<VEC, 64>(mode);
+    }
+}
+
+struct ProfScope {
+    const cbm_handle* h;
+    hipStream_t s;
+    hipEvent_t a = nullptr, b = nullptr;
+    ProfScope(const cbm_handle* h_, hipStream_t s_, cbm_launch_record rec) : h(h_), s(s_) {
+        if (!h->profiling) return;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+            a = b = nullptr;
+            return;
+        }
+        hipEventRecord(a, s);
+        h->prof_records.push_back(rec);
+    }
+    ~ProfScope() {
+        if (!a) return;
+        hipEventRecord(b, s);
+        h->prof_events.push_back(a);
+        h->prof_events.push_back(b);
+    }
+};
+
+}  // namespace
+
+cbm_status cbm_upload(cbm_handle* h) {
+    int dev = h->opts.device;
+    int cur = -1;
+    HIP_TRY(hipGetDevice(&cur), CBM_ERR_HIP);
+    if (dev < 0) dev = cur;
+    if (cur != dev) HIP_TRY(hipSetDevice(dev), CBM_ERR_HIP);
+    h->device = dev;
+    auto up = [&](auto** dptr, const auto& vec) -> cbm_status {
+        using T = std::remove_reference_t<decltype(**dptr)>;
+        *dptr = nullptr;
+        size_t bytes = vec.size() * sizeof(T);
+        if (bytes == 0) bytes = sizeof(T);  // keep every pointer valid
+        HIP_TRY(hipMalloc((void**)dptr, bytes), CBM_ERR_ALLOC);
+        if (!vec.empty())
+            HIP_TRY(hipMemcpy(*dptr, vec.data(), vec.size() * sizeof(T), hipMemcpyHostToDevice), CBM_ERR_HIP);
+        return CBM_OK;
+    };
+    cbm_status st = CBM_OK;
+    if ((st = up(&h->d_tasks, h->tasks)) != CBM_OK || (st = up(&h->d_comb, h->comb)) != CBM_OK ||
+        (st = up(&h->d_dcol, h->dcol)) != CBM_OK || (st = up(&h->d_dinv, h->dinv)) != CBM_OK ||
+        (st = up(&h->d_internal, h->internal_rows)) != CBM_OK) {
+        cbm_release_device(h);
+        if (cur != dev) hipSetDevice(cur);
+        return st;
+    }
+    h->on_device = true;
+    if (cur != dev) hipSetDevice(cur);
+    return CBM_OK;
+}
+
+void cbm_release_device(cbm_handle* h) {
+    for (void* e : h->prof_events) hipEventDestroy((hipEvent_t)e);
+    h->prof_events.clear();
+    if (h->d_tasks) hipFree(h->d_tasks);
+    if (h->d_comb) hipFree(h->d_comb);
+    if (h->d_dcol) hipFree(h->d_dcol);
+    if (h->d_dinv) hipFree(h->d_dinv);
+    if (h->d_internal) hipFree(h->d_internal);
+    if (h->d_scratch) hipFree(h->d_scratch);
+    h->d_tasks = h->d_comb = nullptr;
+    h->d_dcol = nullptr;
+    h->d_dinv = nullptr;
+    h->d_internal = nullptr;
+    h->d_scratch = nullptr;
+    h->scratch_k = 0;
+    h->on_device = false;
+}
+
+cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
+                              CbmEpilogue epi, void* stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    int cur = -1;
+    HIP_TRY(hipGetDevice(&cur), CBM_ERR_HIP);
+    if (cur != h->device) return CBM_ERR_STATE;  // the caller's current device must be the handle's
+
+    // scratch rows for split rows, sized for this k on first use
+    const int64_t ld_scratch = ((int64_t)k + 3) & ~(int64_t)3;
+    if (h->num_slots > 0 && h->scratch_k < ld_scratch) {
+        if (h->d_scratch) hipFree(h->d_scratch);
+        h->d_scratch = nullptr;
+        h->scratch_k = 0;
+        HIP_TRY(hipMalloc((void**)&h->d_scratch, (size_t)h->num_slots * ld_scratch * sizeof(float)), CBM_ERR_ALLOC);
+        h->scratch_k = ld_scratch;
+    }
+
+    // widest loads the operands allow
+    auto aligned = [&](int v) {
+        const uintptr_t mask = (uintptr_t)v * 4 - 1;
+        return k % v == 0 && ldx % v == 0 && ldy % v == 0 && ((uintptr_t)X & mask) == 0 && ((uintptr_t)Y & mask) == 0;
+    };
+    const int vec = aligned(4) ? 4 : aligned(2) ? 2 : 1;
+    int lanes = 4;
+    while (lanes < 64 && lanes * vec < k) lanes *= 2;
+    const int mode = (int)epi;
+    const Variant var = vec == 4 ? pick_lanes<4>(lanes, mode) : vec == 2 ? pick_lanes<2>(lanes, mode)
+                                                                         : pick_lanes<1>(lanes, mode);
+    if (h->profiling) {
+        for (void* e : h->prof_events) hipEventDestroy((hipEvent_t)e);
+        h->prof_events.clear();
+        h->prof_records.clear();
+    }
+    const LaunchCtx ctx{h, X, ldx, k, Y, ldy, ld_scratch, stream};
+    const int64_t rowb = 4 * (int64_t)k;
+    const int64_t per_delta = rowb + 4 + (mode != 0 ? 4 : 0);
+    for (size_t l = 0; l < h->levels.size(); ++l) {
+        const CbmLevel& L = h->levels[l];
+        if (L.task_count > 0) {
+            cbm_launch_record rec{};
+            rec.kind = 0;
+            rec.level = (int32_t)l + 1;
+            rec.tasks = L.task_count;
+            rec.deltas = L.deltas;
+            rec.algorithmic_bytes = L.deltas * per_delta + (L.rows_written + L.segments + L.parent_reads) * rowb +
+                                    L.task_count * (int64_t)sizeof(CbmTask) + (mode != 0 ? 4 * L.rows_written : 0);
+            ProfScope ps(h, stream, rec);
+            var.level(ctx, L);
+        }
+        if (L.comb_count > 0) {
+            cbm_launch_record rec{};
+            rec.kind = 2;
+            rec.level = (int32_t)l + 1;
+            rec.tasks = L.comb_count;
+            rec.algorithmic_bytes = (L.comb_segments + L.comb_parent_reads + L.comb_count) * rowb +
+                                    L.comb_count * (int64_t)sizeof(CbmTask);
+            ProfScope ps(h, stream, rec);
+            var.combine(ctx, L);
+        }
+    }
+    if (mode != 0 && !h->internal_rows.empty()) {
+        const int64_t nr = (int64_t)h->internal_rows.size();
+        cbm_launch_record rec{};
+        rec.kind = 3;
+        rec.tasks = nr;
+        rec.algorithmic_bytes = nr * (2 * rowb + 8);
+        ProfScope ps(h, stream, rec);
+        dim3 grid((unsigned)((nr + 3) / 4));
+        if (mode == 1)
+            hipLaunchKernelGGL(cbm_rowscale_kernel<1>, grid, dim3(256), 0, stream, h->d_internal, nr, Y, ldy,
+                               h->d_dinv, k);
+        else
+            hipLaunchKernelGGL(cbm_rowscale_kernel<2>, grid, dim3(256), 0, stream, h->d_internal, nr, Y, ldy,
+                               h->d_dinv, k);
+    }
+    HIP_TRY(hipGetLastError(), CBM_ERR_HIP);
+    return CBM_OK;
+}

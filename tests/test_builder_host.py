@@ -1,0 +1,185 @@
+"""Host logic of libcbm (no GPU): the library loads and exports the declared
+symbols, the builder's tree/deltas satisfy the paper's invariants and, in exact
+mode, reach the oracle's optimal tree weight; error paths return status codes."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2409_02208_amd as cbm
+import workloads as wl
+from oracle import cbm_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _csr(rows):
+    rowptr = np.zeros(len(rows) + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum([len(r) for r in rows])
+    colidx = np.array([c for r in rows for c in sorted(r)], dtype=np.int32)
+    return rowptr, colidx
+
+
+def _random_rows(rng, m, n, density):
+    return [sorted(np.flatnonzero(rng.random(n) < density).tolist()) for _ in range(m)]
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "cbm.h")).read()
+    declared = set(re.findall(r"\b(cbm_[a-z0-9_]+)\s*\(", header))
+    declared -= {"cbm_launch_record"}
+    assert declared == set(cbm.EXPORTS), declared ^ set(cbm.EXPORTS)
+    lib = ctypes.CDLL(cbm.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert cbm.cbm_status_string(0) == "ok"
+    assert "CSR" in cbm.cbm_status_string(2)
+
+
+def _check_invariants(m, n, rowptr, colidx, h, alpha, self_loops):
+    s = cbm.cbm_stats(h)
+    t = cbm.cbm_get_tree(h)
+    rp, ci = cbm.cbm_decompress(h)
+    rows = orc.adjacency_lists(m, rowptr, colidx, add_self_loops=self_loops)
+    want_rp, want_ci = _csr([sorted(r) for r in rows[1:]])
+    assert np.array_equal(rp, want_rp) and np.array_equal(ci, want_ci)           # Eq. (2) round trip
+    nnz = int(want_rp[-1])
+    assert s["nnz"] == nnz
+    assert s["num_delta_plus"] == t["nplus"].sum() and s["num_delta_minus"] == t["nminus"].sum()
+    assert s["num_delta_plus"] + s["num_delta_minus"] <= nnz                     # Property 1
+    assert s["scalar_ops"] <= nnz                                                # Property 2
+    parent, level = t["parent"], t["level"]
+    assert s["num_roots"] == int((parent < 0).sum())
+    for x in range(m):
+        y = int(parent[x])
+        nx = len(rows[x + 1])
+        if y < 0:
+            assert level[x] == 1 and t["nplus"][x] == nx and t["nminus"][x] == 0
+            continue
+        assert level[x] == level[y] + 1                                          # acyclic, reaches vertex 0
+        w = len(rows[x + 1] ^ rows[y + 1])
+        assert t["nplus"][x] + t["nminus"][x] == w
+        assert w <= nx - max(alpha, 1)                                           # alpha rule; draws -> virtual
+        assert 1 + w <= nx                                                       # Property 2, per row
+    assert s["depth"] == (int(level.max()) if m else 0)
+    return s
+
+
+@pytest.mark.parametrize("alpha", [0, 1, 3])
+@pytest.mark.parametrize("self_loops", [False, True])
+def test_invariants_random(alpha, self_loops):
+    rng = np.random.default_rng(alpha * 2 + self_loops)
+    m = n = 60
+    rows = _random_rows(rng, m, n, 0.2)
+    rows[4] = []
+    rows[11] = list(rows[10])
+    rowptr, colidx = _csr(rows)
+    h = cbm.cbm_build(m, n, rowptr, colidx, alpha=alpha, add_self_loops=self_loops, host_only=True)
+    _check_invariants(m, n, rowptr, colidx, h, alpha, self_loops)
+    cbm.cbm_free(h)
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_exact_mode_reaches_the_minimum_spanning_tree_weight(seed):
+    # hub_cap = max_candidates = max_depth = unlimited, alpha = 0: Prim on all useful edges
+    rng = np.random.default_rng(40 + seed)
+    m, n = 40, 30
+    rows = _random_rows(rng, m, n, 0.35)
+    rows[7] = list(rows[6])
+    rowptr, colidx = _csr(rows)
+    h = cbm.cbm_build(m, n, rowptr, colidx, max_depth=-1, hub_cap=-1, max_candidates=-1, host_only=True)
+    s = _check_invariants(m, n, rowptr, colidx, h, 0, False)
+    R = orc.adjacency_lists(m, rowptr, colidx)
+    W = orc.hamming_distance_graph(R)
+    r = orc.mst_rooted_at_virtual(W)
+    assert s["num_delta_plus"] + s["num_delta_minus"] == sum(int(W[r[x], x]) for x in range(1, m + 1))
+
+
+def test_depth_cap_and_pruning_options():
+    g = wl.tiny_graph()
+    full = cbm.cbm_stats(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=-1, host_only=True))
+    for cap in (1, 2, 5):
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=cap, host_only=True)
+        s = _check_invariants(g.n, g.n, g.rowptr, g.colidx, h, 0, False)
+        assert s["depth"] <= cap
+        assert s["num_delta_plus"] + s["num_delta_minus"] >= full["num_delta_plus"] + full["num_delta_minus"]
+    s1 = cbm.cbm_stats(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=1, host_only=True))
+    assert s1["num_roots"] == g.n and s1["num_delta_plus"] == g.nnz and s1["num_delta_minus"] == 0  # plain CSR
+    s2 = cbm.cbm_stats(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=10 ** 6, host_only=True))
+    assert s2["num_roots"] == g.n and s2["depth"] == 1
+
+
+def test_special_shapes():
+    # lower-triangular: the chain; depth capped by default, exact when unlimited
+    m = 50
+    rowptr, colidx = _csr([list(range(i + 1)) for i in range(m)])
+    h = cbm.cbm_build(m, m, rowptr, colidx, max_depth=-1, host_only=True)
+    s = _check_invariants(m, m, rowptr, colidx, h, 0, False)
+    assert s["num_delta_plus"] == m and s["num_delta_minus"] == 0 and s["depth"] == m
+    # identical rows: one stored in full, the others cost one op each
+    row = [1, 4, 5, 7]
+    rowptr, colidx = _csr([row] * 9)
+    s = cbm.cbm_stats(cbm.cbm_build(9, 8, rowptr, colidx, host_only=True))
+    assert s["num_delta_plus"] == 4 and s["num_delta_minus"] == 0 and s["scalar_ops"] == 4 + 8
+    # empty matrix, empty rows, single row, rectangular
+    for rows, n in ([], 5), ([[]] * 3, 4), ([[0, 2]], 3), ([[0, 1, 2, 3, 4, 5, 6], [0, 1, 2, 3, 4, 5]], 7):
+        rowptr, colidx = _csr(rows)
+        h = cbm.cbm_build(len(rows), n, rowptr, colidx, host_only=True)
+        _check_invariants(len(rows), n, rowptr, colidx, h, 0, False)
+
+
+def test_long_rows_are_split_into_segments():
+    rng = np.random.default_rng(0)
+    n = 5000
+    rows = [sorted(rng.choice(n, size=1800, replace=False).tolist()), [1, 2, 3], []]
+    rowptr, colidx = _csr(rows)
+    h = cbm.cbm_build(3, n, rowptr, colidx, host_only=True)
+    s = _check_invariants(3, n, rowptr, colidx, h, 0, False)
+    assert s["num_split_rows"] == 1 and s["num_tasks"] == 2 + 4
+
+
+def test_error_paths_return_status_codes():
+    rowptr, colidx = _csr([[0, 1], [1]])
+    with pytest.raises(cbm.CbmError) as e:
+        cbm.cbm_build(2, 2, np.array([0, 2, 1], dtype=np.int64), colidx, host_only=True)
+    assert e.value.status == 2
+    for bad in ([1, 0, 1], [0, 0, 1], [0, 5, 1], [-1, 1, 1]):
+        with pytest.raises(cbm.CbmError) as e:
+            cbm.cbm_build(2, 2, rowptr, np.array(bad, dtype=np.int32), host_only=True)
+        assert e.value.status == 2
+    with pytest.raises(cbm.CbmError) as e:
+        cbm.cbm_build(2, 2, rowptr, colidx, alpha=-1, host_only=True)
+    assert e.value.status == 1
+    with pytest.raises(cbm.CbmError) as e:  # self-loops need a square matrix
+        cbm.cbm_build(2, 3, rowptr, colidx, add_self_loops=True, host_only=True)
+    assert e.value.status == 1
+    lib = ctypes.CDLL(cbm.LIB_PATH)
+    assert lib.cbm_build(ctypes.c_int64(2), ctypes.c_int64(2), None, None, None, None) == 1
+    lib.cbm_free(None)  # NULL-safe
+    # a host-only handle refuses products (no device arrays) instead of computing anything on the CPU
+    h = cbm.cbm_build(2, 2, rowptr, colidx, host_only=True)
+    lib.cbm_spmm.argtypes = [ctypes.c_void_p] * 2 + [ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
+                                                     ctypes.c_void_p]
+    assert lib.cbm_spmm(h.ptr, 16, 4, 4, 32, 4, None) == 6
+    assert lib.cbm_spmm(h.ptr, None, 4, 4, 32, 4, None) == 1
+    assert lib.cbm_spmm(h.ptr, 16, 2, 4, 32, 4, None) == 1
+
+
+@pytest.mark.parametrize("name,kw", [("citation", dict(n=3000, p_in=3e-3, p_out=2e-4)), ("collaboration", dict(n=3000)),
+                                     ("protein", dict(n=1200, knn=20)), ("rmat", dict(scale=10, edge_factor=8))])
+def test_invariants_on_reduced_workloads(name, kw):
+    g = wl.make_graph(name, **kw)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=1, host_only=True)
+    s = cbm.cbm_stats(h)
+    rp, ci = cbm.cbm_decompress(h)
+    # A v I rebuilt exactly
+    rows = np.repeat(np.arange(g.n), np.diff(g.rowptr))
+    want = np.unique(np.concatenate((rows.astype(np.int64) * g.n + g.colidx, np.arange(g.n, dtype=np.int64) * (g.n + 1))))
+    got = np.repeat(np.arange(g.n, dtype=np.int64), np.diff(rp)) * g.n + ci
+    assert np.array_equal(got, want)
+    assert s["num_delta_plus"] + s["num_delta_minus"] <= s["nnz"] and s["scalar_ops"] <= s["nnz"]
+    t = cbm.cbm_get_tree(h)
+    comp = t["parent"] >= 0
+    assert np.all(t["level"][comp] == t["level"][t["parent"][comp]] + 1)

@@ -1,0 +1,300 @@
+"""GPU parity: libcbm (through its C ABI binding) against the CPU oracle, element
+by element, on the same seeded inputs.  Integer-valued features must match
+bit for bit; Gaussian features within 1e-5 row-scaled max-norm relative error."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import cbm_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+
+    import paper_2409_02208_amd as cbm
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch, cbm
+
+
+def row_scaled_error(got: np.ndarray, ref: np.ndarray, scale_from: np.ndarray = None) -> float:
+    """max_i ( max_j |got - ref|[i,j] / max_j |ref|[i,j] ); rows whose reference is all zero must be exact.
+    ``scale_from`` supplies the row scale when ``ref`` went through a ReLU: the rounding error of a row is
+    relative to its pre-activation magnitude, which the clipping may have removed from ``ref``."""
+    got = got.astype(np.float64)
+    diff = np.abs(got - ref).max(axis=1) if ref.size else np.zeros(0)
+    scale = np.abs(ref if scale_from is None else scale_from).max(axis=1) if ref.size else np.zeros(0)
+    zero = scale == 0
+    assert np.all(diff[zero] == 0), "rows with an all-zero reference must be exactly zero"
+    return float((diff[~zero] / scale[~zero]).max()) if np.any(~zero) else 0.0
+
+
+def _csr(rows):
+    rowptr = np.zeros(len(rows) + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum([len(r) for r in rows])
+    colidx = np.array([c for r in rows for c in sorted(r)], dtype=np.int32)
+    return rowptr, colidx
+
+
+def _run(env, fn_name, h, X, m, poison=True):
+    torch, cbm = env
+    Xd = torch.from_numpy(X).cuda()
+    Y = torch.full((m, X.shape[1]), float("nan"), device="cuda") if poison else torch.empty((m, X.shape[1]), device="cuda")
+    getattr(cbm, fn_name)(h, Xd, Y)
+    torch.cuda.synchronize()
+    return Y.cpu().numpy()
+
+
+SMALL = {
+    "tiny": {},
+    "citation": dict(n=6000, p_in=1.5e-3, p_out=1e-4),
+    "collaboration": dict(n=20000),
+    "protein": dict(n=6000, knn=60),
+    "rmat": dict(scale=14, edge_factor=16),
+}
+
+
+@pytest.fixture(scope="module")
+def graphs():
+    return {name: wl.make_graph(name, **kw) for name, kw in SMALL.items()}
+
+
+@pytest.mark.parametrize("name", wl.CONFIGS)
+@pytest.mark.parametrize("k", [16, 128])
+def test_spmm_integer_features_bit_exact(env, graphs, name, k):
+    torch, cbm = env
+    g = graphs[name]
+    X = wl.integer_features(g.n, k, g.meta["seed"])
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx)
+    got = _run(env, "cbm_spmm", h, X, g.n)
+    ref = orc.spmm_csr(g.rowptr, g.colidx, X)
+    assert np.abs(ref).max() < 2 ** 24
+    assert np.array_equal(got.astype(np.float64), ref)
+    again = _run(env, "cbm_spmm", h, X, g.n)
+    assert np.array_equal(got, again)
+
+
+@pytest.mark.parametrize("name", wl.CONFIGS)
+@pytest.mark.parametrize("k", [3, 16, 64, 112, 128, 256, 500])
+def test_spmm_normalized_gaussian(env, graphs, name, k):
+    torch, cbm = env
+    g = graphs[name]
+    X = wl.gaussian_features(g.n, k, g.meta["seed"])
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True)
+    got = _run(env, "cbm_spmm_normalized", h, X, g.n)
+    ref = orc.spmm_csr_normalized(g.rowptr, g.colidx, X)
+    assert row_scaled_error(got, ref) <= TOL
+    got_relu = _run(env, "cbm_spmm_normalized_relu", h, X, g.n)
+    assert row_scaled_error(got_relu, np.maximum(ref, 0.0), scale_from=ref) <= TOL
+    plain = _run(env, "cbm_spmm", h, X, g.n)  # (A v I) X on a self-loop handle
+    ref_plain = orc.spmm_csr(g.rowptr, g.colidx, X) + X.astype(np.float64)
+    assert row_scaled_error(plain, ref_plain) <= TOL
+
+
+@pytest.mark.parametrize("opts", [dict(alpha=2), dict(alpha=16), dict(max_depth=1), dict(max_depth=3),
+                                  dict(max_depth=-1), dict(hub_cap=4), dict(max_candidates=1),
+                                  dict(hub_cap=-1, max_candidates=-1, max_depth=-1)])
+def test_every_valid_tree_gives_the_same_product(env, graphs, opts):
+    torch, cbm = env
+    for name in ("tiny", "collaboration"):
+        g = graphs[name]
+        X = wl.integer_features(g.n, 32, 5)
+        ref = orc.spmm_csr(g.rowptr, g.colidx, X)
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, **opts)
+        assert np.array_equal(_run(env, "cbm_spmm", h, X, g.n).astype(np.float64), ref)
+        Xg = wl.gaussian_features(g.n, 32, 5)
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, **opts)
+        assert row_scaled_error(_run(env, "cbm_spmm_normalized", h, Xg, g.n),
+                                orc.spmm_csr_normalized(g.rowptr, g.colidx, Xg)) <= TOL
+
+
+def test_regular_graph_normalized_bit_exact(env):
+    # degree 3 + self-loop: d = 4, d^-1/2 = 1/2 exactly, so the normalised product of integers is exact
+    torch, cbm = env
+    n = 4096
+    edges = [(i, (i + 1) % n) for i in range(n)] + [(i, (i + n // 2) % n) for i in range(n // 2)]
+    adj = [set() for _ in range(n)]
+    for u, v in edges:
+        adj[u].add(v)
+        adj[v].add(u)
+    rowptr, colidx = _csr(adj)
+    X = wl.integer_features(n, 64, 3)
+    h = cbm.cbm_build(n, n, rowptr, colidx, add_self_loops=True)
+    got = _run(env, "cbm_spmm_normalized", h, X, n)
+    assert np.array_equal(got.astype(np.float64), orc.spmm_csr_normalized(rowptr, colidx, X))
+
+
+def test_lower_triangular_chain_is_cumsum(env):
+    torch, cbm = env
+    m = 300
+    rowptr, colidx = _csr([list(range(i + 1)) for i in range(m)])
+    X = wl.integer_features(m, 8, 1)
+    want = np.cumsum(X.astype(np.float64), axis=0)
+    for depth in (-1, 0, 4):
+        h = cbm.cbm_build(m, m, rowptr, colidx, max_depth=depth)
+        s = cbm.cbm_stats(h)
+        assert s["depth"] == (m if depth == -1 else 16 if depth == 0 else 4)
+        assert np.array_equal(_run(env, "cbm_spmm", h, X, m).astype(np.float64), want)
+
+
+def test_split_rows_and_empty_rows(env):
+    torch, cbm = env
+    rng = np.random.default_rng(0)
+    n = 6000
+    dense_row = sorted(rng.choice(n, size=3000, replace=False).tolist())
+    near = sorted(set(dense_row[:2900]) | {5, 7})  # compresses against the split row
+    rows = [dense_row, near, [], [1, 2, 3], sorted(rng.choice(n, size=1025, replace=False).tolist())] + [[]] * 3
+    rows += [sorted(rng.choice(n, size=int(s), replace=False).tolist()) for s in rng.integers(0, 40, size=n - len(rows))]
+    rowptr, colidx = _csr(rows)
+    for k in (4, 100, 256):
+        X = wl.integer_features(n, k, 2)
+        h = cbm.cbm_build(n, n, rowptr, colidx)
+        s = cbm.cbm_stats(h)
+        assert s["num_split_rows"] >= 2
+        assert np.array_equal(_run(env, "cbm_spmm", h, X, n).astype(np.float64), orc.spmm_csr(rowptr, colidx, X))
+        Xg = wl.gaussian_features(n, k, 2)
+        h = cbm.cbm_build(n, n, rowptr, colidx, add_self_loops=True)
+        assert row_scaled_error(_run(env, "cbm_spmm_normalized", h, Xg, n),
+                                orc.spmm_csr_normalized(rowptr, colidx, Xg)) <= TOL
+
+
+def test_degenerate_shapes(env):
+    torch, cbm = env
+    # empty matrix
+    h = cbm.cbm_build(0, 5, np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32))
+    X = torch.ones((5, 4), device="cuda")
+    Y = torch.empty((0, 4), device="cuda")
+    cbm.cbm_spmm(h, X, Y)
+    # all rows empty: Y must be written with zeros
+    rowptr, colidx = _csr([[]] * 7)
+    h = cbm.cbm_build(7, 5, rowptr, colidx)
+    got = _run(env, "cbm_spmm", h, np.ones((5, 4), dtype=np.float32), 7)
+    assert np.array_equal(got, np.zeros((7, 4), dtype=np.float32))
+    # rectangular, k = 1 (the matrix-vector product of Eq. (6)), single row
+    rng = np.random.default_rng(1)
+    rows = [sorted(np.flatnonzero(rng.random(37) < 0.3).tolist()) for _ in range(90)]
+    rowptr, colidx = _csr(rows)
+    X = wl.integer_features(37, 1, 0)
+    h = cbm.cbm_build(90, 37, rowptr, colidx)
+    assert np.array_equal(_run(env, "cbm_spmm", h, X, 90).astype(np.float64), orc.spmm_csr(rowptr, colidx, X))
+    rowptr, colidx = _csr([[0, 2]])
+    h = cbm.cbm_build(1, 3, rowptr, colidx)
+    X = np.array([[1, 2], [3, 4], [5, 6]], dtype=np.float32)
+    assert np.array_equal(_run(env, "cbm_spmm", h, X, 1), np.array([[6, 8]], dtype=np.float32))
+    # isolated node in the normalised product: A v I row is {x}, d = 1, output = input row
+    rowptr, colidx = _csr([[1], [0], []])
+    h = cbm.cbm_build(3, 3, rowptr, colidx, add_self_loops=True)
+    X = np.array([[2.0, 4.0], [6.0, 8.0], [3.0, 5.0]], dtype=np.float32)
+    got = _run(env, "cbm_spmm_normalized", h, X, 3)
+    np.testing.assert_allclose(got, [[4.0, 6.0], [4.0, 6.0], [3.0, 5.0]], rtol=1e-6)
+
+
+def test_strided_and_misaligned_operands(env, graphs):
+    torch, cbm = env
+    g = graphs["collaboration"]
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx)
+    k = 48
+    X = wl.integer_features(g.n, k, 9)
+    ref = orc.spmm_csr(g.rowptr, g.colidx, X)
+    # leading dimensions larger than k (a column slice of a wider tensor)
+    Xw = torch.zeros((g.n, 80), device="cuda")
+    Xw[:, 8:8 + k] = torch.from_numpy(X).cuda()
+    Yw = torch.full((g.n, 64), float("nan"), device="cuda")
+    cbm.cbm_spmm(h, Xw[:, 8:8 + k], Yw[:, 4:4 + k])
+    torch.cuda.synchronize()
+    assert np.array_equal(Yw[:, 4:4 + k].cpu().numpy().astype(np.float64), ref)
+    assert bool(torch.isnan(Yw[:, :4]).all()) and bool(torch.isnan(Yw[:, 4 + k:]).all())  # nothing else touched
+    # pointers that are only 4-byte / 8-byte aligned select the narrower-load variants
+    for off in (1, 2):
+        cbm.cbm_spmm(h, Xw[:, off:off + k], Yw[:, off:off + k])
+        torch.cuda.synchronize()
+        want = orc.spmm_csr(g.rowptr, g.colidx, Xw[:, off:off + k].cpu().numpy())
+        assert np.array_equal(Yw[:, off:off + k].cpu().numpy().astype(np.float64), want)
+
+
+def test_argument_errors_on_device_handle(env, graphs):
+    torch, cbm = env
+    g = graphs["tiny"]
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx)  # no self-loops
+    X = torch.zeros((g.n, 8), device="cuda")
+    Y = torch.zeros((g.n, 8), device="cuda")
+    with pytest.raises(cbm.CbmError) as e:
+        cbm.cbm_spmm_normalized(h, X, Y)
+    assert e.value.status == 6
+
+
+@pytest.mark.parametrize("M,N,K", [(1000, 64, 500), (777, 3, 64), (513, 112, 256), (256, 256, 256), (130, 33, 7),
+                                   (1, 1, 1), (300, 200, 37)])
+def test_dense_matmul(env, M, N, K):
+    torch, cbm = env
+    rng = np.random.default_rng(M + N + K)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    B = rng.standard_normal((K, N)).astype(np.float32)
+    Cd = torch.full((M, N), float("nan"), device="cuda")
+    cbm.cbm_dense_matmul(torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda(), Cd)
+    torch.cuda.synchronize()
+    ref = A.astype(np.float64) @ B.astype(np.float64)
+    # bound from the arithmetic: K products summed in fp32, |error| <= ~K * 2^-24 * sum|a||b|
+    bound = 2.0 * K * 2.0 ** -24 * (np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64))
+    assert np.all(np.abs(Cd.cpu().numpy() - ref) <= bound + 1e-30)
+    Ai = rng.integers(-4, 5, size=(M, K)).astype(np.float32)
+    Bi = rng.integers(-4, 5, size=(K, N)).astype(np.float32)
+    cbm.cbm_dense_matmul(torch.from_numpy(Ai).cuda(), torch.from_numpy(Bi).cuda(), Cd)
+    torch.cuda.synchronize()
+    assert np.array_equal(Cd.cpu().numpy().astype(np.float64), Ai.astype(np.float64) @ Bi.astype(np.float64))
+
+
+@pytest.mark.parametrize("name,f_in,hidden,f_out", [("citation", 500, 64, 3), ("protein", 256, 256, 112),
+                                                    ("tiny", 16, 8, 4)])
+def test_gcn2_forward(env, graphs, name, f_in, hidden, f_out):
+    torch, cbm = env
+    g = graphs[name]
+    seed = g.meta["seed"]
+    X = wl.gaussian_features(g.n, f_in, seed)
+    W0 = wl.glorot_uniform(f_in, hidden, seed)
+    W1 = wl.glorot_uniform(hidden, f_out, seed)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True)
+    ws = torch.empty(cbm.cbm_gcn2_workspace_bytes(h, f_in, hidden, f_out), dtype=torch.uint8, device="cuda")
+    out = torch.full((g.n, f_out), float("nan"), device="cuda")
+    cbm.cbm_gcn2_forward(h, *(torch.from_numpy(a).cuda() for a in (X, W0, W1)), out, ws)
+    torch.cuda.synchronize()
+    ref = orc.gcn2(g.rowptr, g.colidx, X, W0, W1)
+    assert row_scaled_error(out.cpu().numpy(), ref) <= TOL
+
+
+def test_iterated_products_ping_pong(env, graphs):
+    # X_{t+1} = A X_t, ten times; each iterate is checked against the oracle fed the GPU's previous iterate
+    torch, cbm = env
+    g = graphs["collaboration"]
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=1)
+    cur = torch.from_numpy(wl.gaussian_features(g.n, 32, 4)).cuda()
+    nxt = torch.empty_like(cur)
+    for _ in range(10):
+        prev = cur.cpu().numpy()
+        cbm.cbm_spmm(h, cur, nxt)
+        torch.cuda.synchronize()
+        assert row_scaled_error(nxt.cpu().numpy(), orc.spmm_csr(g.rowptr, g.colidx, prev)) <= TOL
+        scale = float(nxt.abs().max())
+        cur, nxt = nxt / scale, cur  # keep magnitudes bounded; the division is not part of the check
+
+
+def test_profile_records(env, graphs):
+    torch, cbm = env
+    g = graphs["protein"]
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True)
+    s = cbm.cbm_stats(h)
+    cbm.cbm_profile_enable(h, True)
+    X = torch.from_numpy(wl.gaussian_features(g.n, 64, 1)).cuda()
+    Y = torch.empty_like(X)
+    cbm.cbm_spmm_normalized(h, X, Y)
+    torch.cuda.synchronize()
+    recs = cbm.cbm_profile_read(h)
+    levels = [r for r in recs if r["kind"] == 0]
+    assert len(levels) == s["depth"]
+    assert sum(r["deltas"] for r in levels) == s["num_delta_plus"] + s["num_delta_minus"]
+    assert all(r["milliseconds"] > 0 for r in recs)
