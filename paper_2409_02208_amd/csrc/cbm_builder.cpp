@@ -12,6 +12,8 @@
 #include <atomic>
 #include <chrono>
 #include <cmath>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <functional>
 #include <queue>
@@ -173,20 +175,31 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     auto row = [&](int64_t i) { return colidx + rowptr[i]; };
     auto rlen = [&](int64_t i) { return (int64_t)h->rownnz[i]; };
 
+    const bool verbose = std::getenv("CBM_VERBOSE") != nullptr;
+    auto lap = [&, last = t0](const char* what) mutable {
+        auto now = std::chrono::steady_clock::now();
+        if (verbose) std::fprintf(stderr, "[cbm_build] %-22s %.3f s\n", what, std::chrono::duration<double>(now - last).count());
+        last = now;
+    };
+    lap("validate + A v I");
+    // a depth cap of 1 stores every row in full (plain CSR): no candidate search needed
+    const bool search = max_depth != 1 && m > 1;
+
     // ---- transpose: rows holding each column ------------------------------------------
-    std::vector<int64_t> tptr(n + 1, 0);
-    std::vector<int32_t> trow(nnz);
-    for (int64_t p = 0; p < nnz; ++p) ++tptr[colidx[p] + 1];
-    for (int64_t j = 0; j < n; ++j) tptr[j + 1] += tptr[j];
-    {
+    std::vector<int64_t> tptr(search ? n + 1 : 1, 0);
+    std::vector<int32_t> trow(search ? nnz : 0);
+    if (search) {
+        for (int64_t p = 0; p < nnz; ++p) ++tptr[colidx[p] + 1];
+        for (int64_t j = 0; j < n; ++j) tptr[j + 1] += tptr[j];
         std::vector<int64_t> fill(tptr.begin(), tptr.end() - 1);
         for (int64_t i = 0; i < m; ++i)
             for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) trow[fill[colidx[p]]++] = (int32_t)i;
     }
 
+    lap("transpose");
     // ---- candidate parents: rows sharing columns, ranked by exact Hamming distance ------
     std::vector<std::vector<Cand>> cand_per_thread(nthreads);
-    {
+    if (search) {
         std::vector<std::vector<int32_t>> counters(nthreads), touched(nthreads);
         parallel_chunks(nthreads, m, 64, [&](int64_t b, int64_t e, int tid) {
             auto& cnt = counters[tid];
@@ -254,6 +267,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
         });
     }
 
+    lap("candidates");
     // bucket candidate edges by parent: Prim pushes the out-edges of each newly attached row
     std::vector<int64_t> optr(m + 1, 0);
     for (auto& v : cand_per_thread)
@@ -293,6 +307,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
                 if (h->level[ochild[p]] == 0) pq.push({((uint64_t)ow[p] << 1) | 1u, ochild[p], e.x});
         }
     }
+    lap("tree");
     std::vector<int64_t>().swap(optr);
     std::vector<int32_t>().swap(ochild);
     std::vector<int32_t>().swap(ow);
@@ -343,6 +358,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
         }
     });
 
+    lap("delta lists");
     // ---- D^-1/2 of A v I ---------------------------------------------------------------------
     if (h->square_self_loops) {
         h->dinv.resize(m);
@@ -425,6 +441,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
         h->tasks.insert(h->tasks.end(), lt.begin(), lt.end());
     }
 
+    lap("levels + work lists");
     // ---- counters (Properties 1 and 2) -----------------------------------------------------------
     cbm_stats_t& s = h->stats;
     std::memset(&s, 0, sizeof(s));
