@@ -231,10 +231,12 @@ def main():
     avg_bytes = lv["bytes"] / max(1, lv["launches"])
     achieved = avg_bytes / avg_ms / 1e6 if avg_ms > 0 else 0.0
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        with open(tpath) as f:
-            traffic = json.load(f).get(f"{args.workload}_k{k}_alpha{alpha}", {}).get("bytes_per_launch")
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if os.path.exists(tpath):  # measured offline with rocprofv3 --pmc; absent entry -> null
+        for line in open(tpath):
+            f = line.split()
+            if len(f) == 2 and f[0] == f"{args.workload}_k{k}_alpha{alpha}":
+                traffic = int(f[1])
     roofline = dict(bound="hbm", kernel="cbm_level_kernel", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=achieved / HBM_PEAK_GBS, traffic=traffic,
                     avg_launch_ms=avg_ms, launches_per_step=lv["launches"] / max(1, min(args.steps, 20)),
