@@ -61,7 +61,8 @@ def algorithmic_bytes(stats, k, normalized, internal_fixup=True):
     nd = stats["num_delta_plus"] + stats["num_delta_minus"]
     m = stats["m"]
     mc = m - stats["num_roots"]
-    b = nd * (4 * k + 4 + (4 if normalized else 0)) + m * (4 * k + 16 + (4 if normalized else 0)) + mc * 4 * k
+    b = nd * (4 * k + 4 + (4 if normalized else 0)) + m * (4 * k + 4 + (4 if normalized else 0)) + mc * 4 * k
+    b += 16 * stats["num_tasks"]
     if normalized and internal_fixup:
         b += stats["num_internal"] * (8 * k + 8)
     return b

@@ -51,10 +51,11 @@ typedef enum {
  * add_self_loops Compress A v I instead of A (needs m == n).  Required by
  *                cbm_spmm_normalized, whose matrix is D^-1/2 (A + I) D^-1/2.
  * max_depth      Cap on the depth of the compression tree (a row stored in full
- *                has depth 1).  0 = library default (16); -1 = unlimited.  Each
- *                level is one dependent kernel launch, so this is the knob that
- *                trades compression for GPU parallelism.  Any cap yields a valid
- *                CBM (exact product).
+ *                has depth 1).  0 = library default (16); -1 = unlimited.  The
+ *                tree is cut into vertical paths, one work item each; dependent
+ *                kernel launches per product = rounds of paths (cbm_stats), at
+ *                most the depth.  This knob trades compression for GPU
+ *                parallelism.  Any cap yields a valid CBM (exact product).
  * hub_cap        Candidate search: columns with more than hub_cap entries are
  *                not expanded when counting shared columns (their rows are still
  *                compared exactly once they are candidates).  0 = default (512);
@@ -88,16 +89,16 @@ typedef struct {
     int64_t num_split_rows;  /* rows whose delta list is cut into several segments   */
     int64_t bytes_csr;       /* int64 row offsets + int32 columns, no values         */
     int64_t bytes_cbm;       /* packed device arrays of this handle                  */
-    int32_t depth;           /* number of tree levels = dependent launches           */
+    int32_t depth;           /* number of tree levels                                */
     int32_t alpha;
     int32_t add_self_loops;
-    int32_t reserved;
+    int32_t rounds;          /* dependent kernel launches per product (<= depth)      */
     double build_seconds;
 } cbm_stats_t;
 
 /*
  * cbm_build -- compress a binary CSR matrix (Section 2).
- *   m, n      matrix shape; m, n >= 0, n < 2^31, m < 2^31.
+ *   m, n      matrix shape; 0 <= m, n < 2^29.
  *   rowptr    host, m + 1 entries, rowptr[0] = 0, non-decreasing.
  *   colidx    host, rowptr[m] entries; within a row strictly increasing, in [0, n).
  *   opts      host, or NULL for defaults.
@@ -190,9 +191,9 @@ cbm_status cbm_decompress(const cbm_handle* h, int64_t* rowptr, int32_t* colidx)
  * recent product call, up to `cap` records and the total count in *count.
  */
 typedef struct {
-    int32_t kind;           /* 0 = gather/update level, 1 = segment pass, 2 = split-row
-                               combine, 3 = row-scale fix-up, 4 = dense matmul          */
-    int32_t level;          /* tree level for kinds 0 and 2, else 0                    */
+    int32_t kind;           /* 0 = gather/update round, 2 = split-row combine,
+                               3 = row-scale fix-up                                    */
+    int32_t level;          /* round for kinds 0 and 2, else 0                         */
     int64_t tasks;          /* work items in the launch                               */
     int64_t deltas;         /* delta entries gathered by the launch                   */
     int64_t algorithmic_bytes; /* bytes the method itself must move in this launch    */

@@ -40,10 +40,10 @@ class cbm_stats_t(C.Structure):
                 ("num_delta_minus", C.c_int64), ("num_roots", C.c_int64), ("num_internal", C.c_int64),
                 ("scalar_ops", C.c_int64), ("num_tasks", C.c_int64), ("num_split_rows", C.c_int64),
                 ("bytes_csr", C.c_int64), ("bytes_cbm", C.c_int64), ("depth", C.c_int32), ("alpha", C.c_int32),
-                ("add_self_loops", C.c_int32), ("reserved", C.c_int32), ("build_seconds", C.c_double)]
+                ("add_self_loops", C.c_int32), ("rounds", C.c_int32), ("build_seconds", C.c_double)]
 
     def as_dict(self) -> dict:
-        return {f: getattr(self, f) for f, _ in self._fields_ if f != "reserved"}
+        return {f: getattr(self, f) for f, _ in self._fields_}
 
 
 class cbm_launch_record(C.Structure):

@@ -27,6 +27,7 @@ constexpr int32_t kDefaultMaxDepth = 16;
 constexpr int32_t kDefaultHubCap = 512;
 constexpr int32_t kDefaultMaxCand = 8;
 constexpr int32_t kSplitLen = 512;  // delta entries per segment of a split row
+constexpr int32_t kPathMax = 1024;  // entries (deltas + one marker per row) per path work item
 
 template <class F>
 void parallel_chunks(int nthreads, int64_t total, int64_t chunk, F&& fn) {
@@ -99,7 +100,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     const cbm_build_opts& o = h->opts;
     if (o.alpha < 0 || o.max_depth < -1 || o.hub_cap < -1 || o.max_candidates < -1 || o.num_threads < 0)
         return CBM_ERR_INVALID_ARG;
-    if (m >= INT32_MAX || n >= INT32_MAX) return CBM_ERR_UNSUPPORTED;
+    if (m > (int64_t)CBM_ENTRY_INDEX_MASK || n > (int64_t)CBM_ENTRY_INDEX_MASK) return CBM_ERR_UNSUPPORTED;
     if (o.add_self_loops && m != n) return CBM_ERR_INVALID_ARG;
     int nthreads = o.num_threads > 0 ? o.num_threads : (int)std::max(1u, std::thread::hardware_concurrency());
     const int32_t alpha = o.alpha;
@@ -365,80 +366,132 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
         for (int64_t i = 0; i < m; ++i) h->dinv[i] = (float)(1.0 / std::sqrt((double)rlen(i)));
     }
 
-    // ---- levels and GPU work lists -------------------------------------------------------------
+    // ---- paths, rounds and GPU work lists ---------------------------------------------------------
+    // The tree is cut into vertical paths.  A path is ONE work item: its running sum stays in
+    // registers from row to row (c_x = c_y + deltas, Eq. (5)), so only the head of a path waits for
+    // another work item, the one that produced its parent's row.  Paths whose head hangs off a row of
+    // a round-r path run in round r + 1, and every round is one kernel launch: dependent launches
+    // drop from the tree depth to the number of rounds.  The child that continues a path is the one
+    // whose subtree needs the most rounds (a Strahler-number rule), up to kPathMax entries per path.
     int32_t depth = 0;
     for (int64_t x = 0; x < m; ++x) depth = std::max(depth, h->level[x]);
+    auto dlen = [&](int64_t x) { return h->dptr[x + 1] - h->dptr[x]; };
+    auto is_split = [&](int64_t x) { return dlen(x) > kSplitLen; };
+
+    std::vector<int64_t> cptr(m + 1, 0);
+    for (int64_t x = 0; x < m; ++x)
+        if (h->parent[x] >= 0) ++cptr[h->parent[x] + 1];
+    for (int64_t x = 0; x < m; ++x) cptr[x + 1] += cptr[x];
+    std::vector<int32_t> cidx(cptr[m]);
+    {
+        std::vector<int64_t> fill(cptr.begin(), cptr.end() - 1);
+        for (int64_t x = 0; x < m; ++x)
+            if (h->parent[x] >= 0) cidx[fill[h->parent[x]]++] = (int32_t)x;
+    }
+    std::vector<int32_t> order(m);  // rows by level: parents before children
+    {
+        std::vector<int64_t> lpos(depth + 2, 0);
+        for (int64_t x = 0; x < m; ++x) ++lpos[h->level[x] + 1];
+        for (int l = 0; l <= depth; ++l) lpos[l + 1] += lpos[l];
+        for (int64_t x = 0; x < m; ++x) order[lpos[h->level[x]]++] = (int32_t)x;
+    }
+    // bottom-up: rounds needed by the subtree of x, and the child that should continue x's path
+    std::vector<int32_t> rho(m, 1), next(m, -1);
+    for (int64_t i = m - 1; i >= 0; --i) {
+        const int32_t x = order[i];
+        int32_t best = -1, need = 1;
+        if (!is_split(x))
+            for (int64_t q = cptr[x]; q < cptr[x + 1]; ++q) {
+                const int32_t c = cidx[q];
+                if (!is_split(c) && (best < 0 || rho[c] > rho[best])) best = c;
+            }
+        for (int64_t q = cptr[x]; q < cptr[x + 1]; ++q) {
+            const int32_t c = cidx[q];
+            need = std::max(need, c == best ? rho[c] : rho[c] + 1);
+        }
+        rho[x] = need;
+        next[x] = best;
+    }
+    // top-down: rounds, with the cap on entries per path
+    std::vector<int32_t> round(m, 0);
+    std::vector<int64_t> run(m, 0);  // entries of the path up to and including x (deltas + one marker per row)
+    int32_t nrounds = 0;
+    for (int64_t i = 0; i < m; ++i) {
+        const int32_t x = order[i];
+        const int32_t y = h->parent[x];
+        const bool continues = y >= 0 && next[y] == x;
+        if (continues) {
+            round[x] = round[y];
+            run[x] = run[y] + dlen(x) + 1;
+        } else {
+            round[x] = y < 0 ? 1 : round[y] + 1;
+            run[x] = dlen(x) + 1;
+        }
+        if (next[x] >= 0 && run[x] + dlen(next[x]) + 1 > kPathMax) next[x] = -1;  // cut: the child heads a new path
+        nrounds = std::max(nrounds, round[x]);
+    }
+    // rows that a row of ANOTHER work item is compressed against keep their unscaled sum in Y
     std::vector<uint8_t> internal(m, 0);
-    for (int64_t x = 0; x < m; ++x)
-        if (h->parent[x] >= 0) internal[h->parent[x]] = 1;
-    for (int64_t x = 0; x < m; ++x)
+    for (int64_t x = 0; x < m; ++x) {
+        const int64_t nc = cptr[x + 1] - cptr[x];
+        internal[x] = nc > 1 || (nc == 1 && next[x] < 0);
         if (internal[x]) h->internal_rows.push_back((int32_t)x);
+    }
 
-    std::vector<int64_t> lcount(depth + 1, 0);
-    for (int64_t x = 0; x < m; ++x) ++lcount[h->level[x]];
-    std::vector<std::vector<int32_t>> by_level(depth + 1);
-    for (int l = 1; l <= depth; ++l) by_level[l].reserve(lcount[l]);
-    for (int64_t x = 0; x < m; ++x) by_level[h->level[x]].push_back((int32_t)x);
-
-    h->levels.assign(depth, CbmLevel{});
+    h->levels.assign(nrounds, CbmLevel{});
     h->tasks.clear();
     h->comb.clear();
+    h->stream.clear();
+    h->stream.reserve((size_t)(h->dptr[m] + m));
     h->num_slots = 0;
     int64_t split_rows = 0;
-    // segments of every split row go in front of level 1: they depend on nothing
-    std::vector<CbmTask> segs;
-    for (int l = 1; l <= depth; ++l) {
-        for (int32_t x : by_level[l]) {
-            int64_t len = h->dptr[x + 1] - h->dptr[x];
-            if (len <= kSplitLen) continue;
+    std::vector<std::vector<CbmTask>> rtasks(nrounds + 1), rcomb(nrounds + 1);
+    for (int64_t i = 0; i < m; ++i) {
+        const int32_t x = order[i];
+        const int32_t y = h->parent[x];
+        if (y >= 0 && next[y] == x) continue;  // not a head
+        CbmLevel& R = h->levels[round[x] - 1];
+        if (is_split(x)) {
             ++split_rows;
-            int64_t nseg = (len + kSplitLen - 1) / kSplitLen;
-            CbmTask c{x, h->parent[x], (uint32_t)h->num_slots, (uint32_t)nseg | (internal[x] ? CBM_TASK_INTERNAL : 0u)};
-            h->comb.push_back(c);  // regrouped by level below
+            const int64_t len = dlen(x), nseg = (len + kSplitLen - 1) / kSplitLen;
+            const int64_t base = (int64_t)h->stream.size();
+            h->stream.insert(h->stream.end(), h->dcol.begin() + h->dptr[x], h->dcol.begin() + h->dptr[x + 1]);
+            rcomb[round[x]].push_back({x, y, (uint32_t)h->num_slots, (uint32_t)nseg | (internal[x] ? CBM_TASK_INTERNAL : 0u)});
+            R.comb_segments += nseg;
+            R.comb_parent_reads += y >= 0;
             for (int64_t s = 0; s < nseg; ++s) {
-                int64_t b = h->dptr[x] + s * kSplitLen;
-                int64_t e = std::min<int64_t>(h->dptr[x + 1], b + kSplitLen);
-                segs.push_back({(int32_t)(h->num_slots + s), -1, (uint32_t)b, (uint32_t)(e - b) | CBM_TASK_SEGMENT});
+                const int64_t b = s * kSplitLen, e = std::min<int64_t>(len, b + kSplitLen);
+                rtasks[1].push_back({(int32_t)(h->num_slots + s), -1, (uint32_t)(base + b), (uint32_t)(e - b) | CBM_TASK_SEGMENT});
+                h->levels[0].deltas += e - b;
+                ++h->levels[0].segments;
             }
             h->num_slots += nseg;
+            continue;
         }
+        const int64_t start = (int64_t)h->stream.size();
+        for (int32_t v = x; v >= 0; v = next[v]) {
+            h->stream.insert(h->stream.end(), h->dcol.begin() + h->dptr[v], h->dcol.begin() + h->dptr[v + 1]);
+            h->stream.push_back((uint32_t)v | CBM_ENTRY_MARK | (internal[v] ? CBM_ENTRY_INTERNAL : 0u));
+            R.deltas += dlen(v);
+            ++R.rows_written;
+        }
+        rtasks[round[x]].push_back({x, y, (uint32_t)start, (uint32_t)((int64_t)h->stream.size() - start)});
+        R.parent_reads += y >= 0;
     }
-    // comb[] was filled level by level already (outer loop over l), record the ranges
-    {
-        int64_t pos = 0;
-        for (int l = 1; l <= depth; ++l) {
-            CbmLevel& L = h->levels[l - 1];
-            L.comb_begin = pos;
-            while (pos < (int64_t)h->comb.size() && h->level[h->comb[pos].row] == l) {
-                L.comb_segments += h->comb[pos].len_flags & CBM_TASK_LEN_MASK;
-                L.comb_parent_reads += h->comb[pos].parent >= 0;
-                ++pos;
-            }
-            L.comb_count = pos - L.comb_begin;
-        }
-    }
-    for (int l = 1; l <= depth; ++l) {
-        CbmLevel& L = h->levels[l - 1];
-        L.task_begin = (int64_t)h->tasks.size();
-        std::vector<CbmTask> lt;
-        if (l == 1) {
-            lt = std::move(segs);
-            L.segments = (int64_t)lt.size();
-        }
-        for (int32_t x : by_level[l]) {
-            int64_t len = h->dptr[x + 1] - h->dptr[x];
-            if (len > kSplitLen) continue;
-            lt.push_back({x, h->parent[x], (uint32_t)h->dptr[x], (uint32_t)len | (internal[x] ? CBM_TASK_INTERNAL : 0u)});
-            ++L.rows_written;
-            L.parent_reads += h->parent[x] >= 0;
-        }
+    if ((int64_t)h->stream.size() >= (int64_t)UINT32_MAX) return CBM_ERR_UNSUPPORTED;
+    for (int r = 1; r <= nrounds; ++r) {
+        CbmLevel& R = h->levels[r - 1];
+        auto& lt = rtasks[r];
         // longest first: wave-mates get similar lengths and the tail of the launch is short
         std::stable_sort(lt.begin(), lt.end(), [](const CbmTask& a, const CbmTask& b2) {
             return (a.len_flags & CBM_TASK_LEN_MASK) > (b2.len_flags & CBM_TASK_LEN_MASK);
         });
-        for (auto& t : lt) L.deltas += t.len_flags & CBM_TASK_LEN_MASK;
-        L.task_count = (int64_t)lt.size();
+        R.task_begin = (int64_t)h->tasks.size();
+        R.task_count = (int64_t)lt.size();
         h->tasks.insert(h->tasks.end(), lt.begin(), lt.end());
+        R.comb_begin = (int64_t)h->comb.size();
+        R.comb_count = (int64_t)rcomb[r].size();
+        h->comb.insert(h->comb.end(), rcomb[r].begin(), rcomb[r].end());
     }
 
     lap("levels + work lists");
@@ -462,9 +515,10 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     s.num_tasks = (int64_t)h->tasks.size();
     s.num_split_rows = split_rows;
     s.bytes_csr = 8 * (m + 1) + 4 * in_rowptr[m];
-    s.bytes_cbm = 4 * nd + (int64_t)sizeof(CbmTask) * (int64_t)(h->tasks.size() + h->comb.size()) +
+    s.bytes_cbm = 4 * (int64_t)h->stream.size() + (int64_t)sizeof(CbmTask) * (int64_t)(h->tasks.size() + h->comb.size()) +
                   4 * (int64_t)h->internal_rows.size() + 4 * (int64_t)h->dinv.size();
     s.depth = depth;
+    s.rounds = nrounds;
     s.alpha = alpha;
     s.add_self_loops = o.add_self_loops != 0;
     s.build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();

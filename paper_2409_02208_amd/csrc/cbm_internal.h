@@ -6,11 +6,14 @@
 
 #include "cbm.h"
 
-// One GPU work item: gather `len` signed delta columns starting at dcol[start],
-// add the parent's finished row, write row `row`.
-//   parent  >= 0: row whose result is added first;  -1: none (virtual null row).
-//   len     low 24 bits = number of delta entries; high bits = CBM_TASK_* flags.
-// A delta entry is a column index with the sign in bit 31 (set = Delta-).
+// One GPU work item: start from the parent's finished row, then walk `len` entries of the
+// entry stream beginning at stream[start].
+//   parent  >= 0: row whose result is loaded first;  -1: none (virtual null row).
+//   len     low 24 bits = number of entries; high bits = CBM_TASK_* flags.
+// An entry is either a delta -- a column index with the sign in bit 31 (set = Delta-): gather that
+// row of X -- or a marker (CBM_ENTRY_MARK): store the running sum as row (entry & index mask) of Y
+// and keep going; the next rows of the path continue from the same registers.
+// A SEGMENT task has no markers: its sum goes to scratch row `row` when the entries end.
 struct CbmTask {
     int32_t row;
     int32_t parent;
@@ -22,11 +25,15 @@ constexpr uint32_t CBM_TASK_LEN_MASK = 0x00ffffffu;
 constexpr uint32_t CBM_TASK_INTERNAL = 0x01000000u;  // some row is compressed against this one
 constexpr uint32_t CBM_TASK_SEGMENT = 0x02000000u;   // `row` is a scratch slot, not a matrix row
 constexpr uint32_t CBM_DELTA_MINUS = 0x80000000u;
+constexpr uint32_t CBM_ENTRY_MARK = 0x40000000u;      // entry stores a row instead of gathering one
+constexpr uint32_t CBM_ENTRY_INTERNAL = 0x20000000u;  // marker: another work item reads this row, keep it unscaled
+constexpr uint32_t CBM_ENTRY_INDEX_MASK = 0x1fffffffu;
 
 struct CbmLevel {
-    int64_t task_begin = 0, task_count = 0;        // into tasks[]: whole rows of this level (+ all segments, level 1)
-    int64_t comb_begin = 0, comb_count = 0;        // into comb[]: split rows of this level
-    int64_t deltas = 0;                            // delta entries gathered by the level's main launch
+    // one ROUND of dependent work (the struct keeps its first name: a round of single-row paths is a tree level)
+    int64_t task_begin = 0, task_count = 0;        // into tasks[]: paths headed in this round (+ all segments, round 1)
+    int64_t comb_begin = 0, comb_count = 0;        // into comb[]: split rows of this round
+    int64_t deltas = 0;                            // delta entries gathered by the round's main launch
     int64_t parent_reads = 0;                      // tasks in the main launch with a parent
     int64_t rows_written = 0;                      // matrix rows written by the main launch
     int64_t segments = 0;                          // segment tasks in the main launch
@@ -46,12 +53,13 @@ struct cbm_handle {
     std::vector<int32_t> level;    // 1 = stored in full
     std::vector<int32_t> nplus, nminus;
     std::vector<int64_t> dptr;     // m + 1
-    std::vector<uint32_t> dcol;    // Delta+ then Delta- of each row, sign in bit 31
+    std::vector<uint32_t> dcol;    // Delta+ then Delta- of each row, sign in bit 31 (host copy, by row)
+    std::vector<uint32_t> stream;  // the same deltas in work-item order, with row markers (uploaded)
     std::vector<float> dinv;       // d_x^-1/2 (square_self_loops only)
     std::vector<CbmTask> tasks;
     std::vector<CbmTask> comb;     // split rows: start = first scratch slot, len = number of segments
     std::vector<int32_t> internal_rows;
-    std::vector<CbmLevel> levels;  // levels[0] is tree level 1
+    std::vector<CbmLevel> levels;  // levels[0] is round 1
     int64_t num_slots = 0;         // scratch rows needed by split rows
     cbm_stats_t stats{};
 
@@ -60,7 +68,7 @@ struct cbm_handle {
     bool on_device = false;
     CbmTask* d_tasks = nullptr;
     CbmTask* d_comb = nullptr;
-    uint32_t* d_dcol = nullptr;
+    uint32_t* d_stream = nullptr;
     float* d_dinv = nullptr;
     int32_t* d_internal = nullptr;
     mutable float* d_scratch = nullptr;  // num_slots x scratch_k floats, sized on first use

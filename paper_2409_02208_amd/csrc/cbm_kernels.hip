@@ -51,37 +51,31 @@ __device__ __forceinline__ void st(float* p, const Vec<VEC>& x) {
 }
 
 // MODE 0: Y = A X.  MODE 1: Y = D^-1/2 (A v I) D^-1/2 X.  MODE 2: MODE 1 then max(., 0).
-// In MODE 1/2 a row that other rows are compressed against (CBM_TASK_INTERNAL) is
-// written unscaled, because its children add its unscaled sum (the row scale
-// belongs to the update step, Section 2.2); cbm_rowscale_kernel scales those rows
-// once every level is done.
-template <int VEC, int LANES, int MODE>
-__device__ __forceinline__ void write_row(const CbmTask& tk, Vec<VEC> acc, float* Y, int64_t ldy, float* scratch,
-                                          int64_t ld_scratch, const float* __restrict__ dinv, int c0) {
-    float* dst;
-    if (tk.len_flags & CBM_TASK_SEGMENT) {
-        dst = scratch + (int64_t)tk.row * ld_scratch + c0;
-    } else {
-        dst = Y + (int64_t)tk.row * ldy + c0;
-        if (MODE != 0 && !(tk.len_flags & CBM_TASK_INTERNAL)) {
-            const float s = dinv[tk.row];
+// In MODE 1/2 a row that ANOTHER work item is compressed against (INTERNAL) is written
+// unscaled, because that work item adds its unscaled sum (the row scale belongs to the update
+// step, Section 2.2); cbm_rowscale_kernel scales those rows once every round is done.
+template <int VEC, int MODE>
+__device__ __forceinline__ void store_row(float* dst, Vec<VEC> acc, bool scale, float s) {
+    if (MODE != 0 && scale) {
 #pragma unroll
-            for (int c = 0; c < VEC; ++c) {
-                acc.v[c] *= s;
-                if (MODE == 2) acc.v[c] = fmaxf(acc.v[c], 0.0f);
-            }
+        for (int c = 0; c < VEC; ++c) {
+            acc.v[c] *= s;
+            if (MODE == 2) acc.v[c] = fmaxf(acc.v[c], 0.0f);
         }
     }
     st<VEC>(dst, acc);
 }
 
+// One work item = one path of the compression tree (or one segment of a split row): start from
+// the parent's row, walk the entry stream; a delta entry gathers a row of X, a marker entry stores
+// the running sum as a finished row of Y and the walk goes on from the same registers.
 template <int VEC, int LANES, int MODE>
 __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restrict__ tasks, int64_t ntasks,
-                                                        const uint32_t* __restrict__ dcol,
+                                                        const uint32_t* __restrict__ stream,
                                                         const float* __restrict__ X, int64_t ldx, float* Y,
                                                         int64_t ldy, float* scratch, int64_t ld_scratch,
                                                         const float* __restrict__ dinv, int k) {
-    constexpr int G = 64 / LANES;               // rows per wave
+    constexpr int G = 64 / LANES;               // work items per wave
     constexpr int U = LANES < 8 ? LANES : 8;    // X rows in flight per group
     const int lane = threadIdx.x & 63;
     const int sub = lane / LANES;
@@ -99,14 +93,15 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
     for (int c = 0; c < VEC; ++c) acc.v[c] = 0.0f;
     if (tk.parent >= 0 && colok) acc = ld<VEC>(Y + (int64_t)tk.parent * ldy + c0);
 
-    const uint32_t* dc = dcol + tk.start;
+    const uint32_t* es = stream + tk.start;
     for (uint32_t i = 0; i < len; i += LANES) {
+        // each lane fetches one entry; for a delta its weight is +-d_col^-1/2, for a marker d_row^-1/2
         uint32_t e = 0;
         float wgt = 0.0f;
         if (i + sl < len) {
-            e = dc[i + sl];
+            e = es[i + sl];
             if (MODE != 0) {
-                wgt = dinv[e & ~CBM_DELTA_MINUS];
+                wgt = dinv[e & CBM_ENTRY_INDEX_MASK];
                 wgt = (e & CBM_DELTA_MINUS) ? -wgt : wgt;
             }
         }
@@ -116,9 +111,9 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
             uint32_t eu[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                eu[u] = (uint32_t)__shfl((int)e, u0 + u, LANES);
-                if (u0 + u < cnt && colok) {
-                    x[u] = ld<VEC>(X + (int64_t)(eu[u] & ~CBM_DELTA_MINUS) * ldx + c0);
+                eu[u] = (uint32_t)__shfl((int)e, u0 + u, LANES);  // lanes past cnt hold e = 0: a delta of weight 0
+                if (u0 + u < cnt && !(eu[u] & CBM_ENTRY_MARK) && colok) {
+                    x[u] = ld<VEC>(X + (int64_t)(eu[u] & CBM_ENTRY_INDEX_MASK) * ldx + c0);
                 } else {
 #pragma unroll
                     for (int c = 0; c < VEC; ++c) x[u].v[c] = 0.0f;
@@ -126,8 +121,13 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (MODE != 0) {
-                    const float w = __shfl(wgt, u0 + u, LANES);
+                float w = 0.0f;
+                if (MODE != 0) w = __shfl(wgt, u0 + u, LANES);
+                if (eu[u] & CBM_ENTRY_MARK) {
+                    if (colok)
+                        store_row<VEC, MODE>(Y + (int64_t)(eu[u] & CBM_ENTRY_INDEX_MASK) * ldy + c0, acc,
+                                             !(eu[u] & CBM_ENTRY_INTERNAL), w);
+                } else if (MODE != 0) {
 #pragma unroll
                     for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(w, x[u].v[c], acc.v[c]);
                 } else {
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
             }
         }
     }
-    if (colok) write_row<VEC, LANES, MODE>(tk, acc, Y, ldy, scratch, ld_scratch, dinv, c0);
+    if ((tk.len_flags & CBM_TASK_SEGMENT) && colok) st<VEC>(scratch + (int64_t)tk.row * ld_scratch + c0, acc);
 }
 
 // Rows whose delta list was cut into segments: Y[x,:] = Y[r_x,:] + sum of the row's segment sums.
@@ -163,9 +163,8 @@ __global__ __launch_bounds__(256) void cbm_combine_kernel(const CbmTask* __restr
 #pragma unroll
         for (int c = 0; c < VEC; ++c) acc.v[c] += p.v[c];
     }
-    CbmTask out = tk;
-    out.len_flags &= ~CBM_TASK_SEGMENT;
-    write_row<VEC, LANES, MODE>(out, acc, Y, ldy, nullptr, 0, dinv, c0);
+    store_row<VEC, MODE>(Y + (int64_t)tk.row * ldy + c0, acc, !(tk.len_flags & CBM_TASK_INTERNAL),
+                         MODE != 0 ? dinv[tk.row] : 1.0f);
 }
 
 // Deferred row scale of the rows that have children (MODE 1/2 only).
@@ -202,7 +201,7 @@ void launch_level(const LaunchCtx& c, const CbmLevel& L) {
     if (L.task_count > 0) {
         dim3 grid((unsigned)((L.task_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
         hipLaunchKernelGGL((cbm_level_kernel<VEC, LANES, MODE>), grid, dim3(256), 0, c.stream,
-                           c.h->d_tasks + L.task_begin, L.task_count, c.h->d_dcol, c.X, c.ldx, c.Y, c.ldy,
+                           c.h->d_tasks + L.task_begin, L.task_count, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy,
                            c.h->d_scratch, c.ld_scratch, c.h->d_dinv, c.k);
     }
 }
@@ -282,7 +281,7 @@ cbm_status cbm_upload(cbm_handle* h) {
     };
     cbm_status st = CBM_OK;
     if ((st = up(&h->d_tasks, h->tasks)) != CBM_OK || (st = up(&h->d_comb, h->comb)) != CBM_OK ||
-        (st = up(&h->d_dcol, h->dcol)) != CBM_OK || (st = up(&h->d_dinv, h->dinv)) != CBM_OK ||
+        (st = up(&h->d_stream, h->stream)) != CBM_OK || (st = up(&h->d_dinv, h->dinv)) != CBM_OK ||
         (st = up(&h->d_internal, h->internal_rows)) != CBM_OK) {
         cbm_release_device(h);
         if (cur != dev) hipSetDevice(cur);
@@ -298,12 +297,12 @@ void cbm_release_device(cbm_handle* h) {
     h->prof_events.clear();
     if (h->d_tasks) hipFree(h->d_tasks);
     if (h->d_comb) hipFree(h->d_comb);
-    if (h->d_dcol) hipFree(h->d_dcol);
+    if (h->d_stream) hipFree(h->d_stream);
     if (h->d_dinv) hipFree(h->d_dinv);
     if (h->d_internal) hipFree(h->d_internal);
     if (h->d_scratch) hipFree(h->d_scratch);
     h->d_tasks = h->d_comb = nullptr;
-    h->d_dcol = nullptr;
+    h->d_stream = nullptr;
     h->d_dinv = nullptr;
     h->d_internal = nullptr;
     h->d_scratch = nullptr;
@@ -355,8 +354,10 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
             rec.level = (int32_t)l + 1;
             rec.tasks = L.task_count;
             rec.deltas = L.deltas;
+            // per delta: one X row + its entry (+ d^-1/2); per row: one Y write + its marker entry (+ d^-1/2);
+            // per work item: its 16-byte record and, if it has one, the parent's row
             rec.algorithmic_bytes = L.deltas * per_delta + (L.rows_written + L.segments + L.parent_reads) * rowb +
-                                    L.task_count * (int64_t)sizeof(CbmTask) + (mode != 0 ? 4 * L.rows_written : 0);
+                                    L.task_count * (int64_t)sizeof(CbmTask) + (mode != 0 ? 8 : 4) * L.rows_written;
             ProfScope ps(h, stream, rec);
             var.level(ctx, L);
         }

@@ -64,6 +64,7 @@ def _check_invariants(m, n, rowptr, colidx, h, alpha, self_loops):
         assert w <= nx - max(alpha, 1)                                           # alpha rule; draws -> virtual
         assert 1 + w <= nx                                                       # Property 2, per row
     assert s["depth"] == (int(level.max()) if m else 0)
+    assert (1 if m else 0) <= s["rounds"] <= max(s["depth"], 0)
     return s
 
 
@@ -118,6 +119,7 @@ def test_special_shapes():
     h = cbm.cbm_build(m, m, rowptr, colidx, max_depth=-1, host_only=True)
     s = _check_invariants(m, m, rowptr, colidx, h, 0, False)
     assert s["num_delta_plus"] == m and s["num_delta_minus"] == 0 and s["depth"] == m
+    assert s["rounds"] == 1 and s["num_tasks"] == 1  # the whole chain is one path: one work item, one launch
     # identical rows: one stored in full, the others cost one op each
     row = [1, 4, 5, 7]
     rowptr, colidx = _csr([row] * 9)
