@@ -191,8 +191,8 @@ cbm_status cbm_decompress(const cbm_handle* h, int64_t* rowptr, int32_t* colidx)
  * recent product call, up to `cap` records and the total count in *count.
  */
 typedef struct {
-    int32_t kind;           /* 0 = gather/update round, 2 = split-row combine,
-                               3 = row-scale fix-up                                    */
+    int32_t kind;           /* 0 = gather/update round, 1 = segments of split rows,
+                               2 = split-row combine, 3 = row-scale fix-up             */
     int32_t level;          /* round for kinds 0 and 2, else 0                         */
     int64_t tasks;          /* work items in the launch                               */
     int64_t deltas;         /* delta entries gathered by the launch                   */

@@ -26,8 +26,11 @@ namespace {
 constexpr int32_t kDefaultMaxDepth = 16;
 constexpr int32_t kDefaultHubCap = 512;
 constexpr int32_t kDefaultMaxCand = 8;
-constexpr int32_t kSplitLen = 512;  // delta entries per segment of a split row
-constexpr int32_t kPathMax = 1024;  // entries (deltas + one marker per row) per path work item
+constexpr int32_t kSplitLenDefault = 512;  // most delta entries in one segment of a split row
+constexpr int32_t kSplitMinDefault = 128;  // rows with more delta entries than this are split
+constexpr int32_t kPhasesDefault = 4;      // sub-ranges of an XCD's column range, for rows of >= kFineMin entries
+constexpr int32_t kFineMinDefault = 1024;
+constexpr int32_t kPathMaxDefault = 256;  // entries (deltas + one marker per row) per path work item
 
 template <class F>
 void parallel_chunks(int nthreads, int64_t total, int64_t chunk, F&& fn) {
@@ -375,8 +378,11 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     // whose subtree needs the most rounds (a Strahler-number rule), up to kPathMax entries per path.
     int32_t depth = 0;
     for (int64_t x = 0; x < m; ++x) depth = std::max(depth, h->level[x]);
+    const int64_t kPathMax = std::getenv("CBM_PATH_MAX") ? std::atol(std::getenv("CBM_PATH_MAX")) : kPathMaxDefault;
     auto dlen = [&](int64_t x) { return h->dptr[x + 1] - h->dptr[x]; };
-    auto is_split = [&](int64_t x) { return dlen(x) > kSplitLen; };
+    const int64_t kSplitLen = std::getenv("CBM_SPLIT_LEN") ? std::atol(std::getenv("CBM_SPLIT_LEN")) : kSplitLenDefault;
+    const int64_t kSplitMin = std::getenv("CBM_SPLIT_MIN") ? std::atol(std::getenv("CBM_SPLIT_MIN")) : kSplitMinDefault;
+    auto is_split = [&](int64_t x) { return dlen(x) > kSplitMin; };
 
     std::vector<int64_t> cptr(m + 1, 0);
     for (int64_t x = 0; x < m; ++x)
@@ -446,26 +452,50 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     h->num_slots = 0;
     int64_t split_rows = 0;
     std::vector<std::vector<CbmTask>> rtasks(nrounds + 1), rcomb(nrounds + 1);
+    const int kPhases = std::getenv("CBM_PHASES") ? std::atoi(std::getenv("CBM_PHASES")) : kPhasesDefault;
+    const int64_t kFineMin = std::getenv("CBM_FINE_MIN") ? std::atol(std::getenv("CBM_FINE_MIN")) : kFineMinDefault;
+    std::vector<std::vector<CbmTask>> seg_tasks((size_t)CBM_XCD * (kPhases + 1));  // [xcd][phase]; last = unphased
+    h->seg_deltas = 0;
     for (int64_t i = 0; i < m; ++i) {
         const int32_t x = order[i];
         const int32_t y = h->parent[x];
         if (y >= 0 && next[y] == x) continue;  // not a head
         CbmLevel& R = h->levels[round[x] - 1];
         if (is_split(x)) {
+            // A long row is cut into segments that depend on nothing.  Its entries are re-sorted by column
+            // and cut at the CBM_XCD column-range boundaries first: all segments of one column range run on
+            // one XCD (workgroup id mod 8), so the popular rows of X in that range stay in that XCD's L2.
             ++split_rows;
-            const int64_t len = dlen(x), nseg = (len + kSplitLen - 1) / kSplitLen;
+            const int64_t len = dlen(x);
             const int64_t base = (int64_t)h->stream.size();
             h->stream.insert(h->stream.end(), h->dcol.begin() + h->dptr[x], h->dcol.begin() + h->dptr[x + 1]);
-            rcomb[round[x]].push_back({x, y, (uint32_t)h->num_slots, (uint32_t)nseg | (internal[x] ? CBM_TASK_INTERNAL : 0u)});
+            std::sort(h->stream.begin() + base, h->stream.end(), [](uint32_t a, uint32_t b2) {
+                return (a & CBM_ENTRY_INDEX_MASK) < (b2 & CBM_ENTRY_INDEX_MASK);
+            });
+            const int64_t slot0 = h->num_slots;
+            // Very long rows are cut finer still: each XCD's column range is walked in kPhases sub-ranges, one
+            // after the other, so that at any time an XCD gathers from 1/(8 kPhases) of X and its 4 MiB L2
+            // holds a larger share of the popular rows.  Shorter split rows get one piece per XCD range.
+            const int fine = len >= kFineMin ? kPhases : 1;  // pieces per XCD range
+            const int npieces = CBM_XCD * fine;
+            int64_t pos = 0;
+            for (int f = 0; f < npieces; ++f) {
+                const uint32_t hi = (uint32_t)(((int64_t)(f + 1) * n + npieces - 1) / npieces);  // columns < hi
+                int64_t end = pos;
+                while (end < len && (h->stream[base + end] & CBM_ENTRY_INDEX_MASK) < hi) ++end;
+                auto& list = seg_tasks[(size_t)(f / fine) * (kPhases + 1) + (fine > 1 ? f % fine : kPhases)];
+                for (int64_t b = pos; b < end; b += kSplitLen) {
+                    const int64_t e = std::min(end, b + kSplitLen);
+                    list.push_back({(int32_t)h->num_slots, -1, (uint32_t)(base + b), (uint32_t)(e - b) | CBM_TASK_SEGMENT});
+                    ++h->num_slots;
+                }
+                pos = end;
+            }
+            const int64_t nseg = h->num_slots - slot0;
+            h->seg_deltas += len;
+            rcomb[round[x]].push_back({x, y, (uint32_t)slot0, (uint32_t)nseg | (internal[x] ? CBM_TASK_INTERNAL : 0u)});
             R.comb_segments += nseg;
             R.comb_parent_reads += y >= 0;
-            for (int64_t s = 0; s < nseg; ++s) {
-                const int64_t b = s * kSplitLen, e = std::min<int64_t>(len, b + kSplitLen);
-                rtasks[1].push_back({(int32_t)(h->num_slots + s), -1, (uint32_t)(base + b), (uint32_t)(e - b) | CBM_TASK_SEGMENT});
-                h->levels[0].deltas += e - b;
-                ++h->levels[0].segments;
-            }
-            h->num_slots += nseg;
             continue;
         }
         const int64_t start = (int64_t)h->stream.size();
@@ -479,13 +509,23 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
         R.parent_reads += y >= 0;
     }
     if ((int64_t)h->stream.size() >= (int64_t)UINT32_MAX) return CBM_ERR_UNSUPPORTED;
+    auto longest_first = [](const CbmTask& a, const CbmTask& b2) {
+        return (a.len_flags & CBM_TASK_LEN_MASK) > (b2.len_flags & CBM_TASK_LEN_MASK);
+    };
+    for (int j = 0; j < CBM_XCD; ++j) {  // segment work items first: one block per XCD, phases in order
+        h->seg_begin[j] = (int64_t)h->tasks.size();
+        for (int ph = 0; ph <= kPhases; ++ph) {
+            auto& list = seg_tasks[(size_t)j * (kPhases + 1) + ph];
+            std::stable_sort(list.begin(), list.end(), longest_first);
+            h->tasks.insert(h->tasks.end(), list.begin(), list.end());
+        }
+        h->seg_count[j] = (int64_t)h->tasks.size() - h->seg_begin[j];
+    }
     for (int r = 1; r <= nrounds; ++r) {
         CbmLevel& R = h->levels[r - 1];
         auto& lt = rtasks[r];
         // longest first: wave-mates get similar lengths and the tail of the launch is short
-        std::stable_sort(lt.begin(), lt.end(), [](const CbmTask& a, const CbmTask& b2) {
-            return (a.len_flags & CBM_TASK_LEN_MASK) > (b2.len_flags & CBM_TASK_LEN_MASK);
-        });
+        std::stable_sort(lt.begin(), lt.end(), longest_first);
         R.task_begin = (int64_t)h->tasks.size();
         R.task_count = (int64_t)lt.size();
         h->tasks.insert(h->tasks.end(), lt.begin(), lt.end());

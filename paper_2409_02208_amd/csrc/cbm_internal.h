@@ -28,6 +28,7 @@ constexpr uint32_t CBM_DELTA_MINUS = 0x80000000u;
 constexpr uint32_t CBM_ENTRY_MARK = 0x40000000u;      // entry stores a row instead of gathering one
 constexpr uint32_t CBM_ENTRY_INTERNAL = 0x20000000u;  // marker: another work item reads this row, keep it unscaled
 constexpr uint32_t CBM_ENTRY_INDEX_MASK = 0x1fffffffu;
+constexpr int CBM_XCD = 8;  // accelerator complex dies of an MI355X; workgroup (linear id) b runs on XCD b mod 8
 
 struct CbmLevel {
     // one ROUND of dependent work (the struct keeps its first name: a round of single-row paths is a tree level)
@@ -36,7 +37,6 @@ struct CbmLevel {
     int64_t deltas = 0;                            // delta entries gathered by the round's main launch
     int64_t parent_reads = 0;                      // tasks in the main launch with a parent
     int64_t rows_written = 0;                      // matrix rows written by the main launch
-    int64_t segments = 0;                          // segment tasks in the main launch
     int64_t comb_segments = 0;                     // scratch rows read by the combine launch
     int64_t comb_parent_reads = 0;
 };
@@ -61,6 +61,8 @@ struct cbm_handle {
     std::vector<int32_t> internal_rows;
     std::vector<CbmLevel> levels;  // levels[0] is round 1
     int64_t num_slots = 0;         // scratch rows needed by split rows
+    int64_t seg_begin[CBM_XCD] = {}, seg_count[CBM_XCD] = {};  // segment work items in tasks[], per column range
+    int64_t seg_deltas = 0;        // delta entries gathered by the segment launch
     cbm_stats_t stats{};
 
     // ---- device arrays (owned) ---------------------------------------------------

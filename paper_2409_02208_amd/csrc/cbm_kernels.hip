@@ -12,6 +12,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 
 #include "cbm_internal.h"
 
@@ -69,20 +70,43 @@ __device__ __forceinline__ void store_row(float* dst, Vec<VEC> acc, bool scale, 
 // One work item = one path of the compression tree (or one segment of a split row): start from
 // the parent's row, walk the entry stream; a delta entry gathers a row of X, a marker entry stores
 // the running sum as a finished row of Y and the walk goes on from the same registers.
-template <int VEC, int LANES, int MODE>
+//
+// A group of LANES lanes owns the work item.  Entries are fetched LANES at a time (one coalesced
+// load, two chunks ahead; their d^-1/2 weights one chunk ahead) and broadcast inside the group.
+// X rows are loaded in batches of U; two batches ping-pong so that the loads of batch b+1 are in
+// flight while batch b is accumulated: a long path is a chain of dependent adds, but never a chain
+// of dependent loads.
+// Segment launches map workgroups to work items per XCD: workgroup b runs on XCD b mod 8 and takes
+// its items from that XCD's block of the task list (the segments of one column range of X).
+struct CbmSegMap {
+    int64_t begin[CBM_XCD];
+    int64_t count[CBM_XCD];
+    int use;
+};
+
+template <int VEC, int LANES, int MODE, int UMAX>
 __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restrict__ tasks, int64_t ntasks,
+                                                        const CbmSegMap map,
                                                         const uint32_t* __restrict__ stream,
                                                         const float* __restrict__ X, int64_t ldx, float* Y,
                                                         int64_t ldy, float* scratch, int64_t ld_scratch,
                                                         const float* __restrict__ dinv, int k) {
-    constexpr int G = 64 / LANES;               // work items per wave
-    constexpr int U = LANES < 8 ? LANES : 8;    // X rows in flight per group
+    constexpr int G = 64 / LANES;                  // work items per wave
+    constexpr int U = LANES < UMAX ? LANES : UMAX;  // X rows per batch
+    constexpr int BPC = LANES / U;                  // batches per chunk of entries
     const int lane = threadIdx.x & 63;
     const int sub = lane / LANES;
     const int sl = lane % LANES;
-    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t t = wave * G + sub;
-    if (t >= ntasks) return;  // a whole group leaves together: no lane it exchanges with is gone
+    int64_t t;
+    if (map.use) {
+        const int xcd = blockIdx.x % CBM_XCD;  // gridDim.x is a multiple of 8, so this is the linear id mod 8
+        const int64_t tl = ((int64_t)(blockIdx.x / CBM_XCD) * 4 + (threadIdx.x >> 6)) * G + sub;
+        if (tl >= map.count[xcd]) return;
+        t = map.begin[xcd] + tl;
+    } else {
+        t = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * G + sub;
+        if (t >= ntasks) return;  // a whole group leaves together: no lane it exchanges with is gone
+    }
     const CbmTask tk = tasks[t];
     const uint32_t len = tk.len_flags & CBM_TASK_LEN_MASK;
     const int c0 = (blockIdx.y * LANES + sl) * VEC;
@@ -94,50 +118,73 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
     if (tk.parent >= 0 && colok) acc = ld<VEC>(Y + (int64_t)tk.parent * ldy + c0);
 
     const uint32_t* es = stream + tk.start;
-    for (uint32_t i = 0; i < len; i += LANES) {
-        // each lane fetches one entry; for a delta its weight is +-d_col^-1/2, for a marker d_row^-1/2
-        uint32_t e = 0;
-        float wgt = 0.0f;
-        if (i + sl < len) {
-            e = es[i + sl];
-            if (MODE != 0) {
-                wgt = dinv[e & CBM_ENTRY_INDEX_MASK];
-                wgt = (e & CBM_DELTA_MINUS) ? -wgt : wgt;
+    // lanes past the end of the stream hold entry 0 with weight 0: a delta that is never loaded
+    auto load_e = [&](int chunk) -> uint32_t {
+        const uint32_t idx = (uint32_t)chunk * LANES + sl;
+        return idx < len ? es[idx] : 0u;
+    };
+    auto load_w = [&](uint32_t e, int chunk) -> float {  // +-d_col^-1/2 of a delta, d_row^-1/2 of a marker
+        if (MODE == 0) return 0.0f;
+        const uint32_t idx = (uint32_t)chunk * LANES + sl;
+        if (idx >= len) return 0.0f;
+        const float w = dinv[e & CBM_ENTRY_INDEX_MASK];
+        return (e & CBM_DELTA_MINUS) ? -w : w;
+    };
+    uint32_t e0 = load_e(0), e1 = load_e(1), e2 = load_e(2);
+    float w0 = load_w(e0, 0), w1 = load_w(e1, 1);
+
+    struct Batch {
+        Vec<VEC> x[U];
+        uint32_t e[U];
+        float w[U];
+    };
+    const int nb = (int)((len + U - 1) / U);
+    auto fetch = [&](Batch& S, int b) {
+        if (b > 0 && b % BPC == 0) {  // batch b opens the next chunk: rotate the entry pipeline
+            const int chunk = b / BPC;
+            e0 = e1;
+            w0 = w1;
+            e1 = e2;
+            e2 = load_e(chunk + 2);
+            w1 = load_w(e1, chunk + 1);
+        }
+        const int off = (b % BPC) * U;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            S.e[u] = (uint32_t)__shfl((int)e0, off + u, LANES);
+            S.w[u] = MODE != 0 ? __shfl(w0, off + u, LANES) : 0.0f;
+            if ((uint32_t)(b * U + u) < len && !(S.e[u] & CBM_ENTRY_MARK) && colok) {
+                S.x[u] = ld<VEC>(X + (int64_t)(S.e[u] & CBM_ENTRY_INDEX_MASK) * ldx + c0);
+            } else {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) S.x[u].v[c] = 0.0f;
             }
         }
-        const int cnt = (int)min((uint32_t)LANES, len - i);
-        for (int u0 = 0; u0 < cnt; u0 += U) {
-            Vec<VEC> x[U];
-            uint32_t eu[U];
+    };
+    auto consume = [&](const Batch& S) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                eu[u] = (uint32_t)__shfl((int)e, u0 + u, LANES);  // lanes past cnt hold e = 0: a delta of weight 0
-                if (u0 + u < cnt && !(eu[u] & CBM_ENTRY_MARK) && colok) {
-                    x[u] = ld<VEC>(X + (int64_t)(eu[u] & CBM_ENTRY_INDEX_MASK) * ldx + c0);
-                } else {
+        for (int u = 0; u < U; ++u) {
+            if (S.e[u] & CBM_ENTRY_MARK) {
+                if (colok)
+                    store_row<VEC, MODE>(Y + (int64_t)(S.e[u] & CBM_ENTRY_INDEX_MASK) * ldy + c0, acc,
+                                         !(S.e[u] & CBM_ENTRY_INTERNAL), S.w[u]);
+            } else if (MODE != 0) {
 #pragma unroll
-                    for (int c = 0; c < VEC; ++c) x[u].v[c] = 0.0f;
-                }
-            }
+                for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(S.w[u], S.x[u].v[c], acc.v[c]);
+            } else {
+                const uint32_t sgn = S.e[u] & CBM_DELTA_MINUS;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                float w = 0.0f;
-                if (MODE != 0) w = __shfl(wgt, u0 + u, LANES);
-                if (eu[u] & CBM_ENTRY_MARK) {
-                    if (colok)
-                        store_row<VEC, MODE>(Y + (int64_t)(eu[u] & CBM_ENTRY_INDEX_MASK) * ldy + c0, acc,
-                                             !(eu[u] & CBM_ENTRY_INTERNAL), w);
-                } else if (MODE != 0) {
-#pragma unroll
-                    for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(w, x[u].v[c], acc.v[c]);
-                } else {
-                    const uint32_t sgn = eu[u] & CBM_DELTA_MINUS;
-#pragma unroll
-                    for (int c = 0; c < VEC; ++c)
-                        acc.v[c] += __uint_as_float(__float_as_uint(x[u].v[c]) ^ sgn);
-                }
+                for (int c = 0; c < VEC; ++c) acc.v[c] += __uint_as_float(__float_as_uint(S.x[u].v[c]) ^ sgn);
             }
         }
+    };
+    Batch A, B;
+    if (nb > 0) fetch(A, 0);
+    for (int b = 0; b < nb; b += 2) {
+        if (b + 1 < nb) fetch(B, b + 1);
+        consume(A);
+        if (b + 2 < nb) fetch(A, b + 2);
+        if (b + 1 < nb) consume(B);
     }
     if ((tk.len_flags & CBM_TASK_SEGMENT) && colok) st<VEC>(scratch + (int64_t)tk.row * ld_scratch + c0, acc);
 }
@@ -194,16 +241,35 @@ struct LaunchCtx {
     hipStream_t stream;
 };
 
-template <int VEC, int LANES, int MODE>
+template <int VEC, int LANES, int MODE, int UMAX>
 void launch_level(const LaunchCtx& c, const CbmLevel& L) {
     constexpr int G = 64 / LANES;
     const int ychunks = (c.k + LANES * VEC - 1) / (LANES * VEC);
+    CbmSegMap map{};
     if (L.task_count > 0) {
         dim3 grid((unsigned)((L.task_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
-        hipLaunchKernelGGL((cbm_level_kernel<VEC, LANES, MODE>), grid, dim3(256), 0, c.stream,
-                           c.h->d_tasks + L.task_begin, L.task_count, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy,
+        hipLaunchKernelGGL((cbm_level_kernel<VEC, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream,
+                           c.h->d_tasks + L.task_begin, L.task_count, map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy,
                            c.h->d_scratch, c.ld_scratch, c.h->d_dinv, c.k);
     }
+}
+// all segments of all split rows, one block of work items per XCD
+template <int VEC, int LANES, int MODE, int UMAX>
+void launch_segments(const LaunchCtx& c, const CbmLevel&) {
+    constexpr int G = 64 / LANES;
+    const int ychunks = (c.k + LANES * VEC - 1) / (LANES * VEC);
+    CbmSegMap map{};
+    int64_t most = 0;
+    for (int j = 0; j < CBM_XCD; ++j) {
+        map.begin[j] = c.h->seg_begin[j];
+        map.count[j] = c.h->seg_count[j];
+        most = std::max(most, map.count[j]);
+    }
+    map.use = 1;
+    dim3 grid((unsigned)(CBM_XCD * ((most + 4 * G - 1) / (4 * G))), (unsigned)ychunks);
+    hipLaunchKernelGGL((cbm_level_kernel<VEC, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream, c.h->d_tasks,
+                       (int64_t)c.h->tasks.size(), map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.h->d_scratch,
+                       c.ld_scratch, c.h->d_dinv, c.k);
 }
 template <int VEC, int LANES, int MODE>
 void launch_combine(const LaunchCtx& c, const CbmLevel& L) {
@@ -217,15 +283,15 @@ void launch_combine(const LaunchCtx& c, const CbmLevel& L) {
 
 using LevelFn = void (*)(const LaunchCtx&, const CbmLevel&);
 struct Variant {
-    LevelFn level, combine;
+    LevelFn level, combine, segments;
 };
 
 template <int VEC, int LANES>
 Variant pick_mode(int mode) {
     switch (mode) {
-        case 0: return {launch_level<VEC, LANES, 0>, launch_combine<VEC, LANES, 0>};
-        case 1: return {launch_level<VEC, LANES, 1>, launch_combine<VEC, LANES, 1>};
-        default: return {launch_level<VEC, LANES, 2>, launch_combine<VEC, LANES, 2>};
+        case 0: return {launch_level<VEC, LANES, 0, 8>, launch_combine<VEC, LANES, 0>, launch_segments<VEC, LANES, 0, 8>};
+        case 1: return {launch_level<VEC, LANES, 1, 8>, launch_combine<VEC, LANES, 1>, launch_segments<VEC, LANES, 1, 8>};
+        default: return {launch_level<VEC, LANES, 2, 8>, launch_combine<VEC, LANES, 2>, launch_segments<VEC, LANES, 2, 8>};
     }
 }
 template <int VEC>
@@ -346,6 +412,15 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
     const LaunchCtx ctx{h, X, ldx, k, Y, ldy, ld_scratch, stream};
     const int64_t rowb = 4 * (int64_t)k;
     const int64_t per_delta = rowb + 4 + (mode != 0 ? 4 : 0);
+    if (h->num_slots > 0) {
+        cbm_launch_record rec{};
+        rec.kind = 1;
+        rec.tasks = h->num_slots;
+        rec.deltas = h->seg_deltas;
+        rec.algorithmic_bytes = h->seg_deltas * per_delta + h->num_slots * (rowb + (int64_t)sizeof(CbmTask));
+        ProfScope ps(h, stream, rec);
+        var.segments(ctx, CbmLevel{});
+    }
     for (size_t l = 0; l < h->levels.size(); ++l) {
         const CbmLevel& L = h->levels[l];
         if (L.task_count > 0) {
@@ -356,7 +431,7 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
             rec.deltas = L.deltas;
             // per delta: one X row + its entry (+ d^-1/2); per row: one Y write + its marker entry (+ d^-1/2);
             // per work item: its 16-byte record and, if it has one, the parent's row
-            rec.algorithmic_bytes = L.deltas * per_delta + (L.rows_written + L.segments + L.parent_reads) * rowb +
+            rec.algorithmic_bytes = L.deltas * per_delta + (L.rows_written + L.parent_reads) * rowb +
                                     L.task_count * (int64_t)sizeof(CbmTask) + (mode != 0 ? 8 : 4) * L.rows_written;
             ProfScope ps(h, stream, rec);
             var.level(ctx, L);

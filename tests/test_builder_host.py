@@ -135,11 +135,12 @@ def test_special_shapes():
 def test_long_rows_are_split_into_segments():
     rng = np.random.default_rng(0)
     n = 5000
-    rows = [sorted(rng.choice(n, size=1800, replace=False).tolist()), [1, 2, 3], []]
-    rowptr, colidx = _csr(rows)
-    h = cbm.cbm_build(3, n, rowptr, colidx, host_only=True)
-    s = _check_invariants(3, n, rowptr, colidx, h, 0, False)
-    assert s["num_split_rows"] == 1 and s["num_tasks"] == 2 + 4
+    for size, pieces in ((900, 8), (1800, 32)):  # one piece per XCD column range; 4 sub-ranges each from 1024 entries
+        rows = [sorted(rng.choice(n, size=size, replace=False).tolist()), [1, 2, 3], []]
+        rowptr, colidx = _csr(rows)
+        h = cbm.cbm_build(3, n, rowptr, colidx, host_only=True)
+        s = _check_invariants(3, n, rowptr, colidx, h, 0, False)
+        assert s["num_split_rows"] == 1 and s["num_tasks"] == 2 + pieces
 
 
 def test_error_paths_return_status_codes():
