@@ -2,15 +2,17 @@
 """Benchmark of the CBM product path on one MI355X.
 
 One "step" = one normalised product  Y = D^-1/2 (A + I) D^-1/2 X  through libcbm
-(delta-gather + tree update + row scale, all tree levels) on a seeded synthetic
-graph already resident in HBM.  Default workload: the large power-law graph
-(R-MAT scale 21, edge factor 32) at k = 128.  The same run also times
+(delta-gather + tree update + row scale, every round of the compression tree) on
+a seeded synthetic graph already resident in HBM.  Default workload: the large
+power-law graph (R-MAT scale 21, edge factor 32) at k = 128.  The same run also
+times
   * the same kernels on an all-roots handle (= plain CSR SpMM on the GPU),
   * a two-layer GCN inference (dense X.W on MFMA + two normalised products),
   * the CPU oracle on a bounded row sample, and an OpenMP CSR SpMM on all host cores,
 and checks sampled output rows against the oracle.
 
 Prints ONE JSON line on stdout; progress goes to stderr.
+`--report FILE` instead walks all five synthetic graphs and writes a table.
 """
 from __future__ import annotations
 
@@ -29,7 +31,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
 
-DEFAULTS = {  # workload -> (k, alpha, GCN shape or None)
+DEFAULTS = {  # workload -> k of the timed product, alpha, GCN shape or None
     "tiny": dict(k=16, alpha=0, gcn=(16, 8, 4)),
     "citation": dict(k=500, alpha=2, gcn=(500, 64, 3)),
     "collaboration": dict(k=128, alpha=2, gcn=None),
@@ -53,23 +55,20 @@ def time_steps(torch, fn, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / max(1, steps)
 
 
-def algorithmic_bytes(stats, k, normalized, internal_fixup=True):
-    """Bytes the method itself must move in one product: per delta one X row + its index
-    (+ one d^-1/2 entry when normalised), per row one Y write and its work-item record,
-    per compressed row one parent read; the deferred row scale re-reads and re-writes rows
-    that have children."""
+def algorithmic_bytes(stats, k, normalized):
+    """Bytes the method itself must move in one product: per delta one X row + its 4-byte entry
+    (+ one d^-1/2 value when normalised); per row one Y write + its 4-byte marker entry (+ d^-1/2);
+    per compressed row one parent-row read.  Work-item records, partial sums of split rows and the
+    deferred row scale are overheads of this implementation, not of the method, and are left out."""
     nd = stats["num_delta_plus"] + stats["num_delta_minus"]
     m = stats["m"]
     mc = m - stats["num_roots"]
-    b = nd * (4 * k + 4 + (4 if normalized else 0)) + m * (4 * k + 4 + (4 if normalized else 0)) + mc * 4 * k
-    b += 16 * stats["num_tasks"]
-    if normalized and internal_fixup:
-        b += stats["num_internal"] * (8 * k + 8)
-    return b
+    extra = 4 if normalized else 0
+    return nd * (4 * k + 4 + extra) + m * (4 * k + 4 + extra) + mc * 4 * k
 
 
 def profile_product(torch, cbm, h, fn, steps):
-    """Per-launch HIP-event timing inside the library, averaged over `steps` steps."""
+    """Per-launch HIP-event timing inside the library, summed per kind over `steps` steps."""
     cbm.cbm_profile_enable(h, True)
     agg = {}
     t_total = 0.0
@@ -87,21 +86,19 @@ def profile_product(torch, cbm, h, fn, steps):
     return agg, t_total / max(1, steps)
 
 
-def sampled_parity(torch, orc, g, X, Y, rows, relu=False):
+def sampled_parity(torch, orc, g, X, Y, rows):
     ref = orc.spmm_csr_normalized(g.rowptr, g.colidx, X, rows=rows)
     got = Y[torch.as_tensor(rows, device="cuda")].cpu().numpy().astype(np.float64)
     scale = np.abs(ref).max(axis=1)
-    if relu:
-        ref = np.maximum(ref, 0)
     diff = np.abs(got - ref).max(axis=1)
     ok = scale > 0
     return float((diff[ok] / scale[ok]).max()) if ok.any() else 0.0
 
 
 def cpu_oracle_baseline(orc, g, X, k, budget_s=15.0):
-    """The oracle as it stands (numpy, one thread per BLAS-free row loop) on a bounded row sample."""
+    """The oracle as it stands (numpy row loop, one thread) on a bounded random row sample."""
     rng = np.random.default_rng(1)
-    d = orc.degrees_with_self_loops(g.rowptr, g.colidx) if g.n <= 300000 else np.diff(g.rowptr) + 1
+    d = np.diff(g.rowptr) + 1  # generators emit no self-loops: d = deg + 1
     probe = rng.choice(g.n, size=min(g.n, 2000), replace=False)
     t0 = time.perf_counter()
     orc.spmm_csr_normalized(g.rowptr, g.colidx, X, rows=probe, d=d)
@@ -112,7 +109,7 @@ def cpu_oracle_baseline(orc, g, X, k, budget_s=15.0):
     orc.spmm_csr_normalized(g.rowptr, g.colidx, X, rows=rows, d=d)
     t = time.perf_counter() - t0
     nnz_s = int((g.rowptr[rows + 1] - g.rowptr[rows]).sum()) + nrows
-    bytes_s = nnz_s * (4 * k + 8) + nrows * (4 * k + 12)
+    bytes_s = nnz_s * (4 * k + 8) + nrows * (4 * k + 8)
     return dict(value=bytes_s / t / 1e9, unit="GB/s", cores=1, kind="oracle",
                 sample=f"{nrows} random rows of {g.n} ({nnz_s} nonzeros of A v I), k={k}, {t:.1f} s",
                 edges_k_per_s=nnz_s * k / t)
@@ -129,43 +126,170 @@ def cpu_csr_omp_baseline(csr_ref, g, X, k, repeats=2):
         best = min(best, time.perf_counter() - t0)
     nnz = g.nnz + g.n
     return dict(ms=best * 1e3, threads=csr_ref.omp_threads(), host_cpus=os.cpu_count(),
-                algorithmic_GBps=(nnz * (4 * k + 8) + g.n * (4 * k + 12)) / best / 1e9,
+                algorithmic_GBps=(nnz * (4 * k + 8) + g.n * (4 * k + 8)) / best / 1e9,
                 edges_k_per_s=nnz * k / best, kind="own OpenMP CSR SpMM, fp32, best of %d" % repeats)
 
 
-def bench_gcn(torch, cbm, wl, orc, name, shape, alpha, steps, warmup, graph=None, handle=None):
+def bench_product(torch, cbm, orc, g, h, hc, Xh, k, steps, warmup, workload, alpha, profile_steps=20):
+    """Time cbm_spmm_normalized on handle h (and on the all-roots handle hc), with the per-launch roofline."""
+    st = cbm.cbm_stats(h)
+    X = torch.from_numpy(Xh).cuda()
+    Y = torch.empty((g.n, k), device="cuda")
+    step = lambda: cbm.cbm_spmm_normalized(h, X, Y)  # noqa: E731
+    ms = time_steps(torch, step, steps, warmup)
+    b_alg = algorithmic_bytes(st, k, True)
+    log(f"{workload} k={k}: cbm_spmm_normalized {ms:.4f} ms/step, {b_alg / ms / 1e6:.1f} GB/s algorithmic")
+
+    # dominant kernel = cbm_level_kernel: kinds 0 (rounds of paths) and 1 (segments of split rows)
+    nprof = max(1, min(steps, profile_steps))
+    agg, ms_prof = profile_product(torch, cbm, h, step, nprof)
+    lv = dict(launches=0, ms=0.0, bytes=0)
+    for kind in (0, 1):
+        for key in lv:
+            lv[key] += agg.get(kind, {}).get(key, 0)
+    avg_ms = lv["ms"] / max(1, lv["launches"])
+    avg_bytes = lv["bytes"] / max(1, lv["launches"])
+    achieved = avg_bytes / avg_ms / 1e6 if avg_ms > 0 else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if os.path.exists(tpath):  # measured offline with rocprofv3 --pmc; absent entry -> null
+        for line in open(tpath):
+            f = line.split()
+            if len(f) == 2 and f[0] == f"{workload}_k{k}_alpha{alpha}":
+                traffic = int(f[1])
+    roofline = dict(bound="hbm", kernel="cbm_level_kernel", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=achieved / HBM_PEAK_GBS, traffic=traffic, avg_launch_ms=avg_ms,
+                    launches_per_step=lv["launches"] / nprof, algorithmic_bytes_per_launch=avg_bytes,
+                    ms_per_step_profiled=ms_prof,
+                    note="algorithmic bytes exceed HBM traffic where gathered rows of X hit in L2 / Infinity Cache, "
+                         "so frac can pass 1; traffic = rocprofv3 FETCH_SIZE+WRITE_SIZE per launch (L2-miss bytes)",
+                    other_kernels_ms_per_step={{2: "combine", 3: "rowscale"}.get(kk, str(kk)): v["ms"] / nprof
+                                               for kk, v in agg.items() if kk not in (0, 1)})
+
+    step()
+    torch.cuda.synchronize()
+    rows = np.random.default_rng(0).choice(g.n, size=min(g.n, 512), replace=False)
+    err = sampled_parity(torch, orc, g, Xh, Y, rows)
+    log(f"{workload} k={k}: sampled parity max row-scaled error {err:.2e} on {len(rows)} rows")
+    assert err <= 1e-5, f"parity failure: {err}"
+
+    gpu_csr, ms_csr = None, None
+    if hc is not None:
+        sc = cbm.cbm_stats(hc)
+        ms_csr = time_steps(torch, lambda: cbm.cbm_spmm_normalized(hc, X, Y), steps, warmup)
+        gpu_csr = dict(ms=ms_csr, algorithmic_GBps=algorithmic_bytes(sc, k, True) / ms_csr / 1e6,
+                       edges_k_per_s=sc["nnz"] * k / ms_csr * 1e3, kind="same kernels, all rows stored in full")
+        log(f"{workload} k={k}: GPU CSR (all-roots handle) {ms_csr:.4f} ms/step; CBM speedup {ms_csr / ms:.3f}x")
+    nd = st["num_delta_plus"] + st["num_delta_minus"]
+    return dict(ms=ms, value=b_alg / ms / 1e6, b_alg=b_alg, roofline=roofline, parity_err=err, rows_checked=len(rows),
+                gpu_csr=gpu_csr, speedup=None if ms_csr is None else ms_csr / ms,
+                edges_k_per_s=st["nnz"] * k / ms * 1e3, deltas_k_per_s=nd * k / ms * 1e3, stats=st)
+
+
+def bench_gcn(torch, cbm, wl, orc, g, h, hc, shape, steps, warmup):
     f_in, hidden, f_out = shape
-    g = graph if graph is not None else wl.make_graph(name)
     seed = g.meta["seed"]
-    h = handle if handle is not None else cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha)
     Xh = wl.gaussian_features(g.n, f_in, seed)
     W0h, W1h = wl.glorot_uniform(f_in, hidden, seed), wl.glorot_uniform(hidden, f_out, seed)
     X, W0, W1 = (torch.from_numpy(a).cuda() for a in (Xh, W0h, W1h))
     out = torch.empty((g.n, f_out), device="cuda")
     ws = torch.empty(cbm.cbm_gcn2_workspace_bytes(h, f_in, hidden, f_out), dtype=torch.uint8, device="cuda")
     ms = time_steps(torch, lambda: cbm.cbm_gcn2_forward(h, X, W0, W1, out, ws), steps, warmup)
-    # dense parts alone, for the MFMA rate
     Z0 = torch.empty((g.n, hidden), device="cuda")
     Z1 = torch.empty((g.n, f_out), device="cuda")
     ms_g0 = time_steps(torch, lambda: cbm.cbm_dense_matmul(X, W0, Z0), steps, warmup)
     ms_g1 = time_steps(torch, lambda: cbm.cbm_dense_matmul(Z0, W1, Z1), steps, warmup)
-    hc = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=1)
-    ms_csr = time_steps(torch, lambda: cbm.cbm_gcn2_forward(hc, X, W0, W1, out, ws), steps, warmup)
+    ms_csr = time_steps(torch, lambda: cbm.cbm_gcn2_forward(hc, X, W0, W1, out, ws), steps, warmup) if hc else None
     cbm.cbm_gcn2_forward(h, X, W0, W1, out, ws)
     torch.cuda.synchronize()
-    rows = np.random.default_rng(2).choice(g.n, size=min(g.n, 256), replace=False)
-    if g.n <= 30000:
+    err = None
+    if g.nnz <= 2_000_000:  # the oracle GCN is a whole-graph computation: small graphs only
+        rows = np.random.default_rng(2).choice(g.n, size=min(g.n, 256), replace=False)
         ref = orc.gcn2(g.rowptr, g.colidx, Xh, W0h, W1h)[rows]
         got = out[torch.as_tensor(rows, device="cuda")].cpu().numpy()
         err = float((np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)).max())
-    else:
-        err = None
+        assert err <= 1e-5, f"GCN parity failure: {err}"
     flops0, flops1 = 2.0 * g.n * f_in * hidden, 2.0 * g.n * hidden * f_out
-    return dict(workload=name, n=g.n, nnz=g.nnz, f_in=f_in, hidden=hidden, f_out=f_out, alpha=alpha,
-                ms=ms, ms_with_csr_handle=ms_csr, ms_matmul0=ms_g0, ms_matmul1=ms_g1,
+    bytes0 = 4.0 * (g.n * f_in + f_in * hidden + g.n * hidden)
+    return dict(workload=g.name, n=g.n, nnz=g.nnz, f_in=f_in, hidden=hidden, f_out=f_out, ms=ms,
+                ms_with_csr_handle=ms_csr, speedup_over_csr_handle=None if ms_csr is None else ms_csr / ms,
+                ms_matmul0=ms_g0, ms_matmul1=ms_g1,
                 matmul0_tflops=flops0 / ms_g0 / 1e9, matmul1_tflops=flops1 / ms_g1 / 1e9,
                 matmul0_frac_of_fp32_mfma_peak=flops0 / ms_g0 / 1e9 / FP32_MFMA_PEAK_TFLOPS,
-                max_row_scaled_error_vs_oracle=err, stats=cbm.cbm_stats(h))
+                matmul0_GBps=bytes0 / ms_g0 / 1e6, max_row_scaled_error_vs_oracle=err)
+
+
+def report(args, torch, cbm, wl, orc, csr_ref):
+    """All five synthetic graphs: absolute GB/s, edges*k/s, ms, roofline fraction, CBM vs GPU CSR, GCN, CPU baselines."""
+    plan = [("tiny", [16]), ("citation", [500]), ("collaboration", [128]), ("protein", [256]), ("rmat", [64, 128])]
+    lines = ["# CBM on one MI355X: five synthetic graphs", "",
+             f"`python bench.py --report <file> --steps {args.steps} --warmup {args.warmup}`; host: {os.cpu_count()} CPUs. "
+             "alg. GB/s = algorithmic bytes / time (can pass the 8 TB/s HBM peak when gathers hit in L2 / Infinity Cache). "
+             "GPU CSR = the same kernels on a handle with every row stored in full. CPU columns: OpenMP CSR SpMM on all "
+             "host cores (fp32) and the numpy oracle on a row sample (1 thread).", "",
+             "| graph | n | nnz(A v I) | k | deltas/nnz | depth / rounds | build s | CBM ms | alg. GB/s | frac of HBM peak | "
+             "edges*k/s | GPU CSR ms | CBM speedup | CPU OMP CSR ms | oracle GB/s | parity err |",
+             "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    gcn_lines = ["", "| graph | GCN shape | CBM ms | with CSR handle ms | speedup | X.W0 ms (TFLOP/s, frac of fp32 MFMA peak) | "
+                 "H.W1 ms | parity err |", "|---|---|---|---|---|---|---|---|"]
+    results = []
+    for name, ks in plan:
+        d = DEFAULTS[name]
+        t0 = time.perf_counter()
+        g = wl.make_graph(name, **({"scale": args.rmat_scale} if name == "rmat" else {}))
+        log(f"graph {name}: n={g.n} nnz={g.nnz} ({time.perf_counter() - t0:.1f} s)")
+        t0 = time.perf_counter()
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=d["alpha"], max_depth=args.max_depth)
+        tb = time.perf_counter() - t0
+        hc = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=1)
+        for k in ks:
+            Xh = wl.gaussian_features(g.n, k, g.meta["seed"])
+            r = bench_product(torch, cbm, orc, g, h, hc, Xh, k, args.steps, args.warmup, name, d["alpha"])
+            cpu = cpu_csr_omp_baseline(csr_ref, g, Xh, k)
+            ob = cpu_oracle_baseline(orc, g, Xh, k, budget_s=5.0)
+            st = r["stats"]
+            nd = st["num_delta_plus"] + st["num_delta_minus"]
+            lines.append(f"| {name} | {g.n} | {st['nnz']} | {k} | {nd / st['nnz']:.3f} | {st['depth']} / {st['rounds']} | {tb:.2f} | "
+                         f"{r['ms']:.4f} | {r['value']:.0f} | {r['value'] / HBM_PEAK_GBS:.3f} | {r['edges_k_per_s']:.3e} | "
+                         f"{r['gpu_csr']['ms']:.4f} | {r['speedup']:.2f}x | {cpu['ms']:.2f} ({cpu['threads']} thr) | "
+                         f"{ob['value']:.2f} | {r['parity_err']:.1e} |")
+            results.append(dict(workload=name, k=k, **{kk: vv for kk, vv in r.items() if kk != "stats"}, stats=st,
+                                cpu_csr_omp=cpu, cpu_oracle=ob))
+        if d["gcn"]:
+            gc = bench_gcn(torch, cbm, wl, orc, g, h, hc, d["gcn"], args.steps, args.warmup)
+            e = gc["max_row_scaled_error_vs_oracle"]
+            gcn_lines.append(f"| {name} | {gc['f_in']}-{gc['hidden']}-{gc['f_out']} | {gc['ms']:.4f} | {gc['ms_with_csr_handle']:.4f} | "
+                             f"{gc['speedup_over_csr_handle']:.2f}x | {gc['ms_matmul0']:.4f} ({gc['matmul0_tflops']:.1f}, "
+                             f"{gc['matmul0_frac_of_fp32_mfma_peak']:.2f}) | {gc['ms_matmul1']:.4f} | "
+                             f"{'n/a (graph too large for the whole-graph oracle)' if e is None else format(e, '.1e')} |")
+            results.append(dict(workload=name, gcn=gc))
+        if name == "collaboration":  # the iterated product X_{t+1} = A X_t of the collaboration config
+            hp = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=d["alpha"], max_depth=args.max_depth)
+            a = torch.from_numpy(wl.gaussian_features(g.n, 128, 5)).cuda()
+            b = torch.empty_like(a)
+
+            def ten():
+                x, y = a, b
+                for _ in range(10):
+                    cbm.cbm_spmm(hp, x, y)
+                    x, y = y, x
+            ms10 = time_steps(torch, ten, max(1, args.steps // 5), 1)
+            sp = cbm.cbm_stats(hp)
+            lines.append(f"| collaboration, A.X x10 (no self-loops) | {g.n} | {g.nnz} | 128 | "
+                         f"{(sp['num_delta_plus'] + sp['num_delta_minus']) / g.nnz:.3f} | {sp['depth']} / {sp['rounds']} | | "
+                         f"{ms10:.4f} (10 products) | | | {g.nnz * 128 * 10 / ms10 * 1e3:.3e} | | | | | |")
+            cbm.cbm_free(hp)
+        cbm.cbm_free(h)
+        cbm.cbm_free(hc)
+    text = "\n".join(lines + gcn_lines) + "\n\nPaper context (not comparable): ~5x SpMM and up to 3x GCN inference over " \
+        "MKL CSR on a 16-core Xeon Gold 6130, relative figures on real datasets.\n"
+    os.makedirs(os.path.dirname(os.path.abspath(args.report)), exist_ok=True)
+    with open(args.report, "w") as f:
+        f.write(text)
+    with open(os.path.splitext(args.report)[0] + ".json", "w") as f:
+        json.dump(results, f, default=float)
+    log("report written to", args.report)
+    print(json.dumps({"report": args.report, "rows": len(results)}), flush=True)
 
 
 def main():
@@ -181,6 +305,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baselines")
     ap.add_argument("--no-gcn", action="store_true", help="skip the GCN inference timing")
     ap.add_argument("--no-csr", action="store_true", help="skip the all-roots (GPU CSR) comparison")
+    ap.add_argument("--report", default="", help="walk all five graphs and write a markdown table to this file")
     ap.add_argument("--probe-copy", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times (calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -204,10 +329,12 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"probe": "copy", "bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4}))
         return
+    if args.report:
+        return report(args, torch, cbm, wl, orc, csr_ref)
+
     d = DEFAULTS[args.workload]
     k = args.k or d["k"]
     alpha = d["alpha"] if args.alpha < 0 else args.alpha
-
     t0 = time.perf_counter()
     g = wl.make_graph(args.workload, **({"scale": args.rmat_scale} if args.workload == "rmat" else {}))
     log(f"graph {g.name}: n={g.n} nnz={g.nnz} max_deg={g.meta['max_degree']} ({time.perf_counter() - t0:.1f} s)")
@@ -216,60 +343,11 @@ def main():
     h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha, max_depth=args.max_depth)
     st = cbm.cbm_stats(h)
     log(f"cbm_build: {time.perf_counter() - t0:.1f} s, deltas={st['num_delta_plus'] + st['num_delta_minus']} "
-        f"of nnz={st['nnz']}, roots={st['num_roots']}, depth={st['depth']}")
-    X = torch.from_numpy(Xh).cuda()
-    Y = torch.empty((g.n, k), device="cuda")
-    step = lambda: cbm.cbm_spmm_normalized(h, X, Y)  # noqa: E731
+        f"of nnz={st['nnz']}, roots={st['num_roots']}, depth={st['depth']}, rounds={st['rounds']}")
+    hc = None if args.no_csr else cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=1)
+    r = bench_product(torch, cbm, orc, g, h, hc, Xh, k, args.steps, args.warmup, args.workload, alpha)
 
-    ms = time_steps(torch, step, args.steps, args.warmup)
-    b_alg = algorithmic_bytes(st, k, True)
-    log(f"cbm_spmm_normalized: {ms:.3f} ms/step, {b_alg / ms / 1e6:.1f} GB/s algorithmic")
-
-    # dominant kernel: the per-level gather/update launch, timed with HIP events inside the library
-    agg, ms_prof = profile_product(torch, cbm, h, step, max(1, min(args.steps, 20)))
-    # kinds 0 (rounds of paths) and 1 (segments of split rows) are launches of the same kernel
-    lv = dict(launches=0, ms=0.0, bytes=0)
-    for kind in (0, 1):
-        for key in lv:
-            lv[key] += agg.get(kind, {}).get(key, 0)
-    avg_ms = lv["ms"] / max(1, lv["launches"])
-    avg_bytes = lv["bytes"] / max(1, lv["launches"])
-    achieved = avg_bytes / avg_ms / 1e6 if avg_ms > 0 else 0.0
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
-    if os.path.exists(tpath):  # measured offline with rocprofv3 --pmc; absent entry -> null
-        for line in open(tpath):
-            f = line.split()
-            if len(f) == 2 and f[0] == f"{args.workload}_k{k}_alpha{alpha}":
-                traffic = int(f[1])
-    roofline = dict(bound="hbm", kernel="cbm_level_kernel", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=achieved / HBM_PEAK_GBS, traffic=traffic,
-                    avg_launch_ms=avg_ms, launches_per_step=lv["launches"] / max(1, min(args.steps, 20)),
-                    algorithmic_bytes_per_launch=avg_bytes, ms_per_step_profiled=ms_prof,
-                    other_kernels_ms_per_step={str(kk): v["ms"] / max(1, min(args.steps, 20))
-                                               for kk, v in agg.items() if kk not in (0, 1)})
-
-    # sampled parity against the oracle, in the launch configuration just timed
-    step()
-    torch.cuda.synchronize()
-    rows = np.random.default_rng(0).choice(g.n, size=min(g.n, 512), replace=False)
-    err = sampled_parity(torch, orc, g, Xh, Y, rows)
-    log(f"sampled parity: max row-scaled error {err:.2e} on {len(rows)} rows")
-    assert err <= 1e-5, f"parity failure: {err}"
-
-    # the same kernels on an all-roots handle: plain CSR SpMM on the GPU
-    gpu_csr, ms_csr = None, float("nan")
-    if not args.no_csr:
-        hc = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=1)
-        sc = cbm.cbm_stats(hc)
-        ms_csr = time_steps(torch, lambda: cbm.cbm_spmm_normalized(hc, X, Y), args.steps, args.warmup)
-        gpu_csr = dict(ms=ms_csr, algorithmic_GBps=algorithmic_bytes(sc, k, True) / ms_csr / 1e6,
-                       edges_k_per_s=sc["nnz"] * k / ms_csr * 1e3, kind="same kernels, all rows stored in full")
-        cbm.cbm_free(hc)
-        log(f"GPU CSR (all-roots handle): {ms_csr:.3f} ms/step; CBM/CSR time ratio {ms / ms_csr:.3f}")
-
-    cpu_baseline = None
-    cpu_csr = None
+    cpu_baseline = cpu_csr = None
     if not args.no_cpu:
         cpu_baseline = cpu_oracle_baseline(orc, g, Xh, k)
         log(f"CPU oracle: {cpu_baseline['value']:.3f} GB/s on {cpu_baseline['sample']}")
@@ -279,21 +357,24 @@ def main():
     gcn = None
     if not args.no_gcn:
         if d["gcn"] is not None:
-            gcn = bench_gcn(torch, cbm, wl, orc, args.workload, d["gcn"], alpha, args.steps, args.warmup, graph=g)
-        else:
-            gcn = bench_gcn(torch, cbm, wl, orc, "citation", DEFAULTS["citation"]["gcn"], DEFAULTS["citation"]["alpha"],
-                            args.steps, args.warmup)
-        log(f"GCN ({gcn['workload']}): {gcn['ms']:.3f} ms (CSR handle {gcn['ms_with_csr_handle']:.3f} ms)")
+            gcn = bench_gcn(torch, cbm, wl, orc, g, h, hc, d["gcn"], args.steps, args.warmup)
+        else:  # the timed graph has no GCN in its configuration: use the citation-like one (PubMed's shape)
+            gc = wl.make_graph("citation")
+            dc = DEFAULTS["citation"]
+            h2 = cbm.cbm_build(gc.n, gc.n, gc.rowptr, gc.colidx, add_self_loops=True, alpha=dc["alpha"])
+            h2c = cbm.cbm_build(gc.n, gc.n, gc.rowptr, gc.colidx, add_self_loops=True, max_depth=1)
+            gcn = bench_gcn(torch, cbm, wl, orc, gc, h2, h2c, dc["gcn"], args.steps, args.warmup)
+        log(f"GCN ({gcn['workload']}): {gcn['ms']:.4f} ms (CSR handle {gcn['ms_with_csr_handle']} ms)")
 
     out = {
         "metric": "CBM normalised product A_hat.X: achieved algorithmic HBM GB/s (with edges*k/s, GPU CSR SpMM and "
                   "2-layer GCN ms alongside)",
-        "value": b_alg / ms / 1e6,
+        "value": r["value"],
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms,
+        "ms_per_step": r["ms"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -301,17 +382,17 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{g.name} ({g.meta['recipe']}), A_hat.X, k={k}", "n": g.n, "nnz": g.nnz, "k": k,
                    "alpha": alpha, "max_depth": args.max_depth or 16, "seed": g.meta["seed"]},
-        "roofline": roofline,
+        "roofline": r["roofline"],
         "cpu_baseline": cpu_baseline,
-        "edges_k_per_s": st["nnz"] * k / ms * 1e3,
-        "deltas_k_per_s": (st["num_delta_plus"] + st["num_delta_minus"]) * k / ms * 1e3,
-        "algorithmic_bytes_per_step": b_alg,
-        "frac_of_hbm_peak": b_alg / ms / 1e6 / HBM_PEAK_GBS,
-        "gpu_csr_spmm": gpu_csr,
-        "cbm_over_csr_speedup": None if args.no_csr else ms_csr / ms,
+        "edges_k_per_s": r["edges_k_per_s"],
+        "deltas_k_per_s": r["deltas_k_per_s"],
+        "algorithmic_bytes_per_step": r["b_alg"],
+        "frac_of_hbm_peak": r["value"] / HBM_PEAK_GBS,
+        "gpu_csr_spmm": r["gpu_csr"],
+        "cbm_over_csr_speedup": r["speedup"],
         "cpu_csr_spmm_omp": cpu_csr,
         "gcn2": gcn,
-        "parity": {"max_row_scaled_error": err, "rows_checked": int(len(rows)), "tolerance": 1e-5},
+        "parity": {"max_row_scaled_error": r["parity_err"], "rows_checked": int(r["rows_checked"]), "tolerance": 1e-5},
         "cbm_stats": st,
         "paper_context": "paper: ~5x SpMM and up to 3x GCN inference over MKL CSR on a 16-core Xeon Gold 6130 "
                          "(relative only, real datasets); not comparable, context only",

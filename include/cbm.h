@@ -51,11 +51,16 @@ typedef enum {
  * add_self_loops Compress A v I instead of A (needs m == n).  Required by
  *                cbm_spmm_normalized, whose matrix is D^-1/2 (A + I) D^-1/2.
  * max_depth      Cap on the depth of the compression tree (a row stored in full
- *                has depth 1).  0 = library default (16); -1 = unlimited.  The
- *                tree is cut into vertical paths, one work item each; dependent
- *                kernel launches per product = rounds of paths (cbm_stats), at
- *                most the depth.  This knob trades compression for GPU
- *                parallelism.  Any cap yields a valid CBM (exact product).
+ *                has depth 1).  -1 = unlimited.  0 = automatic: cap 16, and a
+ *                cost model of the kernels (launch overhead, latency of the
+ *                longest work item, bandwidth) decides whether the tree pays
+ *                for its extra dependent launches at all; on small graphs it
+ *                does not, and every row is then stored in full (the paper's
+ *                own finding for its small citation graphs, Section 3.3).  The
+ *                tree is cut into vertical paths, one work item each;
+ *                dependent kernel launches per product = rounds of paths
+ *                (cbm_stats), at most the depth.  Any value yields a valid CBM
+ *                (exact product).
  * hub_cap        Candidate search: columns with more than hub_cap entries are
  *                not expanded when counting shared columns (their rows are still
  *                compared exactly once they are candidates).  0 = default (512);

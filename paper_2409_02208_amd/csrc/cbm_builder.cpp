@@ -6,8 +6,9 @@
 // materialises the all-pairs distance graph: an edge (y,x) can beat the virtual
 // edge of x only if  w(y,x) = nnz(a_x) + nnz(a_y) - 2|a_x n a_y| < nnz(a_x),
 // i.e. |a_x n a_y| > nnz(a_y)/2, so only rows sharing a column are candidates.
-// The tree is grown Prim-style from the virtual vertex with a cap on depth,
-// because each tree level is one dependent kernel launch on the GPU.
+// The tree is grown Prim-style from the virtual vertex with a cap on depth, then
+// cut into vertical paths (one GPU work item each) whose length is chosen by a
+// small latency/bandwidth cost model of the kernels.
 #include <algorithm>
 #include <atomic>
 #include <chrono>
@@ -30,7 +31,21 @@ constexpr int32_t kSplitLenDefault = 512;  // most delta entries in one segment 
 constexpr int32_t kSplitMinDefault = 128;  // rows with more delta entries than this are split
 constexpr int32_t kPhasesDefault = 4;      // sub-ranges of an XCD's column range, for rows of >= kFineMin entries
 constexpr int32_t kFineMinDefault = 1024;
-constexpr int32_t kPathMaxDefault = 256;  // entries (deltas + one marker per row) per path work item
+
+// Cost model of one product (reference: k = 128, i.e. 512-byte rows).  A launch costs a fixed
+// overhead plus the larger of its bandwidth time and the latency of its longest work item: a work
+// item walks its entries in batches of 8 row loads, so an entry costs about one eighth of a memory
+// round trip.  Measured on MI355X: ~7 us per dependent launch, ~0.2 us per entry, ~6 TB/s.
+constexpr double kLaunchUs = 7.0;
+constexpr double kEntryUs = 0.2;
+constexpr double kBytesPerUs = 6.0e6;
+constexpr double kRefRowBytes = 512.0;
+constexpr int64_t kPathChoices[] = {16, 32, 64, 128, 256, 512};
+
+long env_or(const char* name, long dflt) {
+    const char* v = std::getenv(name);
+    return v ? std::atol(v) : dflt;
+}
 
 template <class F>
 void parallel_chunks(int nthreads, int64_t total, int64_t chunk, F&& fn) {
@@ -96,114 +111,112 @@ struct HeapEdge {
     }
 };
 
-}  // namespace
+struct Builder {
+    cbm_handle* h;
+    int64_t m, n, nnz = 0;
+    int nthreads;
+    int32_t alpha, min_saving, max_depth, hub_cap, max_cand;
+    bool auto_depth;
+    const int64_t* rowptr = nullptr;  // the matrix that is compressed: A, or A v I
+    const int32_t* colidx = nullptr;
+    std::vector<int64_t> own_rowptr;
+    std::vector<int32_t> own_colidx;
+    bool verbose = false;
+    std::chrono::steady_clock::time_point last;
 
-cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const int32_t* in_colidx, cbm_handle* h) {
-    auto t0 = std::chrono::steady_clock::now();
-    const cbm_build_opts& o = h->opts;
-    if (o.alpha < 0 || o.max_depth < -1 || o.hub_cap < -1 || o.max_candidates < -1 || o.num_threads < 0)
-        return CBM_ERR_INVALID_ARG;
-    if (m > (int64_t)CBM_ENTRY_INDEX_MASK || n > (int64_t)CBM_ENTRY_INDEX_MASK) return CBM_ERR_UNSUPPORTED;
-    if (o.add_self_loops && m != n) return CBM_ERR_INVALID_ARG;
-    int nthreads = o.num_threads > 0 ? o.num_threads : (int)std::max(1u, std::thread::hardware_concurrency());
-    const int32_t alpha = o.alpha;
-    const int32_t min_saving = std::max(alpha, 1);  // strict gain at alpha = 0: draws go to the virtual edge
-    const int32_t max_depth = o.max_depth == 0 ? kDefaultMaxDepth : o.max_depth;  // -1 = unlimited
-    const int32_t hub_cap = o.hub_cap == 0 ? kDefaultHubCap : o.hub_cap;
-    const int32_t max_cand = o.max_candidates == 0 ? kDefaultMaxCand : o.max_candidates;
-    h->m = m;
-    h->n = n;
-    h->eff_alpha = alpha;
-    h->eff_max_depth = max_depth;
-    h->eff_hub_cap = hub_cap;
-    h->eff_max_cand = max_cand;
-    h->square_self_loops = o.add_self_loops != 0;
+    const int32_t* row(int64_t i) const { return colidx + rowptr[i]; }
+    int64_t rlen(int64_t i) const { return h->rownnz[i]; }
+    int64_t dlen(int64_t x) const { return h->dptr[x + 1] - h->dptr[x]; }
+    void lap(const char* what) {
+        auto now = std::chrono::steady_clock::now();
+        if (verbose)
+            std::fprintf(stderr, "[cbm_build] %-22s %.3f s\n", what, std::chrono::duration<double>(now - last).count());
+        last = now;
+    }
 
-    // ---- validate -------------------------------------------------------------------
+    cbm_status validate(const int64_t* in_rowptr, const int32_t* in_colidx);
+    void self_loops(const int64_t* in_rowptr, const int32_t* in_colidx);
+    void grow_tree();
+    void all_roots();
+    void delta_lists();
+    // paths
+    std::vector<int64_t> cptr;
+    std::vector<int32_t> cidx, order, rho, cont, next, round;
+    int64_t split_min = 0, split_len = 0;
+    bool is_split(int64_t x) const { return dlen(x) > split_min; }
+    void tree_index();
+    double plan(int64_t path_max, int32_t* nrounds_out);
+    double csr_cost() const;
+    cbm_status emit(int32_t nrounds);
+};
+
+cbm_status Builder::validate(const int64_t* in_rowptr, const int32_t* in_colidx) {
     if (in_rowptr[0] != 0) return CBM_ERR_INVALID_CSR;
     for (int64_t i = 0; i < m; ++i)
         if (in_rowptr[i + 1] < in_rowptr[i]) return CBM_ERR_INVALID_CSR;
-    {
-        std::atomic<bool> bad{false};
-        parallel_chunks(nthreads, m, 4096, [&](int64_t b, int64_t e, int) {
-            for (int64_t i = b; i < e; ++i) {
-                int64_t prev = -1;
-                for (int64_t p = in_rowptr[i]; p < in_rowptr[i + 1]; ++p) {
-                    int64_t c = in_colidx[p];
-                    if (c <= prev || c >= n) {
-                        bad = true;
-                        return;
-                    }
-                    prev = c;
+    std::atomic<bool> bad{false};
+    parallel_chunks(nthreads, m, 4096, [&](int64_t b, int64_t e, int) {
+        for (int64_t i = b; i < e; ++i) {
+            int64_t prev = -1;
+            for (int64_t p = in_rowptr[i]; p < in_rowptr[i + 1]; ++p) {
+                int64_t c = in_colidx[p];
+                if (c <= prev || c >= n) {
+                    bad = true;
+                    return;
                 }
+                prev = c;
             }
-        });
-        if (bad) return CBM_ERR_INVALID_CSR;
-    }
+        }
+    });
+    return bad ? CBM_ERR_INVALID_CSR : CBM_OK;
+}
 
-    // ---- the matrix that is compressed: A, or A v I ------------------------------------
-    std::vector<int64_t> own_rowptr;
-    std::vector<int32_t> own_colidx;
-    const int64_t* rowptr = in_rowptr;
-    const int32_t* colidx = in_colidx;
-    if (o.add_self_loops) {
-        own_rowptr.assign(m + 1, 0);
-        for (int64_t i = 0; i < m; ++i) {
+void Builder::self_loops(const int64_t* in_rowptr, const int32_t* in_colidx) {
+    own_rowptr.assign(m + 1, 0);
+    for (int64_t i = 0; i < m; ++i) {
+        const int32_t* b = in_colidx + in_rowptr[i];
+        const int32_t* e = in_colidx + in_rowptr[i + 1];
+        bool has = std::binary_search(b, e, (int32_t)i);
+        own_rowptr[i + 1] = own_rowptr[i] + (e - b) + (has ? 0 : 1);
+    }
+    own_colidx.resize(own_rowptr[m]);
+    parallel_chunks(nthreads, m, 4096, [&](int64_t b0, int64_t e0, int) {
+        for (int64_t i = b0; i < e0; ++i) {
             const int32_t* b = in_colidx + in_rowptr[i];
             const int32_t* e = in_colidx + in_rowptr[i + 1];
-            bool has = std::binary_search(b, e, (int32_t)i);
-            own_rowptr[i + 1] = own_rowptr[i] + (e - b) + (has ? 0 : 1);
+            int32_t* out = own_colidx.data() + own_rowptr[i];
+            const int32_t* pos = std::lower_bound(b, e, (int32_t)i);
+            out = std::copy(b, pos, out);
+            if (pos == e || *pos != (int32_t)i) *out++ = (int32_t)i;
+            std::copy(pos, e, out);
         }
-        own_colidx.resize(own_rowptr[m]);
-        parallel_chunks(nthreads, m, 4096, [&](int64_t b0, int64_t e0, int) {
-            for (int64_t i = b0; i < e0; ++i) {
-                const int32_t* b = in_colidx + in_rowptr[i];
-                const int32_t* e = in_colidx + in_rowptr[i + 1];
-                int32_t* out = own_colidx.data() + own_rowptr[i];
-                const int32_t* pos = std::lower_bound(b, e, (int32_t)i);
-                out = std::copy(b, pos, out);
-                if (pos == e || *pos != (int32_t)i) *out++ = (int32_t)i;
-                std::copy(pos, e, out);
-            }
-        });
-        rowptr = own_rowptr.data();
-        colidx = own_colidx.data();
-    }
-    const int64_t nnz = rowptr[m];
-    if (nnz >= (int64_t)UINT32_MAX) return CBM_ERR_UNSUPPORTED;
-    h->rownnz.resize(m);
-    for (int64_t i = 0; i < m; ++i) {
-        int64_t len = rowptr[i + 1] - rowptr[i];
-        h->rownnz[i] = (int32_t)len;
-    }
-    auto row = [&](int64_t i) { return colidx + rowptr[i]; };
-    auto rlen = [&](int64_t i) { return (int64_t)h->rownnz[i]; };
+    });
+    rowptr = own_rowptr.data();
+    colidx = own_colidx.data();
+}
 
-    const bool verbose = std::getenv("CBM_VERBOSE") != nullptr;
-    auto lap = [&, last = t0](const char* what) mutable {
-        auto now = std::chrono::steady_clock::now();
-        if (verbose) std::fprintf(stderr, "[cbm_build] %-22s %.3f s\n", what, std::chrono::duration<double>(now - last).count());
-        last = now;
-    };
-    lap("validate + A v I");
-    // a depth cap of 1 stores every row in full (plain CSR): no candidate search needed
-    const bool search = max_depth != 1 && m > 1;
+void Builder::all_roots() {
+    h->parent.assign(m, -1);
+    h->level.assign(m, 1);
+}
 
-    // ---- transpose: rows holding each column ------------------------------------------
-    std::vector<int64_t> tptr(search ? n + 1 : 1, 0);
-    std::vector<int32_t> trow(search ? nnz : 0);
-    if (search) {
-        for (int64_t p = 0; p < nnz; ++p) ++tptr[colidx[p] + 1];
-        for (int64_t j = 0; j < n; ++j) tptr[j + 1] += tptr[j];
+// Candidate parents from shared columns, then Prim growth from the virtual vertex with a depth cap.
+void Builder::grow_tree() {
+    // transpose: rows holding each column
+    std::vector<int64_t> tptr(n + 1, 0);
+    std::vector<int32_t> trow(nnz);
+    for (int64_t p = 0; p < nnz; ++p) ++tptr[colidx[p] + 1];
+    for (int64_t j = 0; j < n; ++j) tptr[j + 1] += tptr[j];
+    {
         std::vector<int64_t> fill(tptr.begin(), tptr.end() - 1);
         for (int64_t i = 0; i < m; ++i)
             for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) trow[fill[colidx[p]]++] = (int32_t)i;
     }
-
     lap("transpose");
-    // ---- candidate parents: rows sharing columns, ranked by exact Hamming distance ------
+
+    // candidate parents: rows sharing columns, ranked by exact Hamming distance
     std::vector<std::vector<Cand>> cand_per_thread(nthreads);
-    if (search) {
+    {
         std::vector<std::vector<int32_t>> counters(nthreads), touched(nthreads);
         parallel_chunks(nthreads, m, 64, [&](int64_t b, int64_t e, int tid) {
             auto& cnt = counters[tid];
@@ -222,7 +235,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
                 int64_t nhub = 0;
                 for (const int32_t* pj = row(x); pj != row(x) + nx; ++pj) {
                     int64_t deg = tptr[*pj + 1] - tptr[*pj];
-                    if (hub_cap >= 0 && deg > hub_cap) {
+                    if (hub_cap >= 0 && deg > hub_cap) {  // a hub column: too many rows to expand
                         ++nhub;
                         continue;
                     }
@@ -270,8 +283,10 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
             }
         });
     }
-
+    std::vector<int64_t>().swap(tptr);
+    std::vector<int32_t>().swap(trow);
     lap("candidates");
+
     // bucket candidate edges by parent: Prim pushes the out-edges of each newly attached row
     std::vector<int64_t> optr(m + 1, 0);
     for (auto& v : cand_per_thread)
@@ -289,36 +304,29 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
             std::vector<Cand>().swap(v);
         }
     }
-
-    // ---- tree: Prim growth from the virtual vertex, depth-capped -------------------------
     h->parent.assign(m, -1);
     h->level.assign(m, 0);
-    {
-        std::vector<HeapEdge> init;
-        init.reserve(m);
-        for (int64_t x = 0; x < m; ++x) init.push_back({(uint64_t)rlen(x) << 1, (int32_t)x, -1});
-        std::priority_queue<HeapEdge, std::vector<HeapEdge>, std::greater<HeapEdge>> pq(std::greater<HeapEdge>(),
-                                                                                        std::move(init));
-        while (!pq.empty()) {
-            HeapEdge e = pq.top();
-            pq.pop();
-            if (h->level[e.x] != 0) continue;
-            int32_t lvl = e.y < 0 ? 1 : h->level[e.y] + 1;
-            h->parent[e.x] = e.y;
-            h->level[e.x] = lvl;
-            if (max_depth > 0 && lvl >= max_depth) continue;  // nothing may hang below the cap
-            for (int64_t p = optr[e.x]; p < optr[e.x + 1]; ++p)
-                if (h->level[ochild[p]] == 0) pq.push({((uint64_t)ow[p] << 1) | 1u, ochild[p], e.x});
-        }
+    std::vector<HeapEdge> init;
+    init.reserve(m);
+    for (int64_t x = 0; x < m; ++x) init.push_back({(uint64_t)rlen(x) << 1, (int32_t)x, -1});
+    std::priority_queue<HeapEdge, std::vector<HeapEdge>, std::greater<HeapEdge>> pq(std::greater<HeapEdge>(),
+                                                                                    std::move(init));
+    while (!pq.empty()) {
+        HeapEdge e = pq.top();
+        pq.pop();
+        if (h->level[e.x] != 0) continue;
+        int32_t lvl = e.y < 0 ? 1 : h->level[e.y] + 1;
+        h->parent[e.x] = e.y;
+        h->level[e.x] = lvl;
+        if (max_depth > 0 && lvl >= max_depth) continue;  // nothing may hang below the cap
+        for (int64_t p = optr[e.x]; p < optr[e.x + 1]; ++p)
+            if (h->level[ochild[p]] == 0) pq.push({((uint64_t)ow[p] << 1) | 1u, ochild[p], e.x});
     }
     lap("tree");
-    std::vector<int64_t>().swap(optr);
-    std::vector<int32_t>().swap(ochild);
-    std::vector<int32_t>().swap(ow);
-    std::vector<int64_t>().swap(tptr);
-    std::vector<int32_t>().swap(trow);
+}
 
-    // ---- delta lists (Eq. (2)) by list merge ------------------------------------------------
+// Delta lists (Eq. (2)) of every tree edge by list merge.
+void Builder::delta_lists() {
     h->nplus.assign(m, 0);
     h->nminus.assign(m, 0);
     parallel_chunks(nthreads, m, 1024, [&](int64_t b, int64_t e, int) {
@@ -335,8 +343,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     });
     h->dptr.assign(m + 1, 0);
     for (int64_t x = 0; x < m; ++x) h->dptr[x + 1] = h->dptr[x] + h->nplus[x] + h->nminus[x];
-    const int64_t nd = h->dptr[m];
-    h->dcol.resize(nd);
+    h->dcol.resize(h->dptr[m]);
     parallel_chunks(nthreads, m, 1024, [&](int64_t b, int64_t e, int) {
         for (int64_t x = b; x < e; ++x) {
             uint32_t* plus = h->dcol.data() + h->dptr[x];
@@ -361,48 +368,34 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
             while (c != ce) *minus++ = (uint32_t)*c++ | CBM_DELTA_MINUS;
         }
     });
-
     lap("delta lists");
-    // ---- D^-1/2 of A v I ---------------------------------------------------------------------
-    if (h->square_self_loops) {
-        h->dinv.resize(m);
-        for (int64_t i = 0; i < m; ++i) h->dinv[i] = (float)(1.0 / std::sqrt((double)rlen(i)));
-    }
+}
 
-    // ---- paths, rounds and GPU work lists ---------------------------------------------------------
-    // The tree is cut into vertical paths.  A path is ONE work item: its running sum stays in
-    // registers from row to row (c_x = c_y + deltas, Eq. (5)), so only the head of a path waits for
-    // another work item, the one that produced its parent's row.  Paths whose head hangs off a row of
-    // a round-r path run in round r + 1, and every round is one kernel launch: dependent launches
-    // drop from the tree depth to the number of rounds.  The child that continues a path is the one
-    // whose subtree needs the most rounds (a Strahler-number rule), up to kPathMax entries per path.
+// Children lists, level order, and for every row the child that should continue its path: the
+// non-split child whose subtree needs the most rounds (a Strahler-number rule, so the number of
+// dependent rounds is as small as the tree allows).
+void Builder::tree_index() {
     int32_t depth = 0;
     for (int64_t x = 0; x < m; ++x) depth = std::max(depth, h->level[x]);
-    const int64_t kPathMax = std::getenv("CBM_PATH_MAX") ? std::atol(std::getenv("CBM_PATH_MAX")) : kPathMaxDefault;
-    auto dlen = [&](int64_t x) { return h->dptr[x + 1] - h->dptr[x]; };
-    const int64_t kSplitLen = std::getenv("CBM_SPLIT_LEN") ? std::atol(std::getenv("CBM_SPLIT_LEN")) : kSplitLenDefault;
-    const int64_t kSplitMin = std::getenv("CBM_SPLIT_MIN") ? std::atol(std::getenv("CBM_SPLIT_MIN")) : kSplitMinDefault;
-    auto is_split = [&](int64_t x) { return dlen(x) > kSplitMin; };
-
-    std::vector<int64_t> cptr(m + 1, 0);
+    cptr.assign(m + 1, 0);
     for (int64_t x = 0; x < m; ++x)
         if (h->parent[x] >= 0) ++cptr[h->parent[x] + 1];
     for (int64_t x = 0; x < m; ++x) cptr[x + 1] += cptr[x];
-    std::vector<int32_t> cidx(cptr[m]);
+    cidx.resize(cptr[m]);
     {
         std::vector<int64_t> fill(cptr.begin(), cptr.end() - 1);
         for (int64_t x = 0; x < m; ++x)
             if (h->parent[x] >= 0) cidx[fill[h->parent[x]]++] = (int32_t)x;
     }
-    std::vector<int32_t> order(m);  // rows by level: parents before children
+    order.resize(m);  // rows by level: parents before children
     {
         std::vector<int64_t> lpos(depth + 2, 0);
         for (int64_t x = 0; x < m; ++x) ++lpos[h->level[x] + 1];
         for (int l = 0; l <= depth; ++l) lpos[l + 1] += lpos[l];
         for (int64_t x = 0; x < m; ++x) order[lpos[h->level[x]]++] = (int32_t)x;
     }
-    // bottom-up: rounds needed by the subtree of x, and the child that should continue x's path
-    std::vector<int32_t> rho(m, 1), next(m, -1);
+    rho.assign(m, 1);
+    cont.assign(m, -1);
     for (int64_t i = m - 1; i >= 0; --i) {
         const int32_t x = order[i];
         int32_t best = -1, need = 1;
@@ -416,11 +409,16 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
             need = std::max(need, c == best ? rho[c] : rho[c] + 1);
         }
         rho[x] = need;
-        next[x] = best;
+        cont[x] = best;
     }
-    // top-down: rounds, with the cap on entries per path
-    std::vector<int32_t> round(m, 0);
-    std::vector<int64_t> run(m, 0);  // entries of the path up to and including x (deltas + one marker per row)
+}
+
+// Cut the tree into paths of at most path_max entries (deltas + one marker per row); fills next[]
+// and round[] and returns the modelled time of one product in microseconds.
+double Builder::plan(int64_t path_max, int32_t* nrounds_out) {
+    next = cont;
+    round.assign(m, 0);
+    std::vector<int64_t> run(m, 0);  // entries of the path up to and including x
     int32_t nrounds = 0;
     for (int64_t i = 0; i < m; ++i) {
         const int32_t x = order[i];
@@ -433,29 +431,79 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
             round[x] = y < 0 ? 1 : round[y] + 1;
             run[x] = dlen(x) + 1;
         }
-        if (next[x] >= 0 && run[x] + dlen(next[x]) + 1 > kPathMax) next[x] = -1;  // cut: the child heads a new path
+        if (next[x] >= 0 && run[x] + dlen(next[x]) + 1 > path_max) next[x] = -1;  // cut: the child heads a new path
         nrounds = std::max(nrounds, round[x]);
     }
+    *nrounds_out = nrounds;
+    // cost: per round, entries gathered and the longest path; split rows add one segment launch and combines
+    std::vector<int64_t> entries(nrounds + 1, 0), rows(nrounds + 1, 0), longest(nrounds + 1, 0), comb(nrounds + 1, 0);
+    int64_t seg_entries = 0;
+    bool fixup = false;
+    for (int64_t i = 0; i < m; ++i) {
+        const int32_t x = order[i];
+        const int r = round[x];
+        const int64_t nc = cptr[x + 1] - cptr[x];
+        fixup = fixup || nc > 1 || (nc == 1 && next[x] < 0);
+        if (is_split(x)) {
+            seg_entries += dlen(x);
+            comb[r] += (dlen(x) + split_len - 1) / split_len + CBM_XCD;
+            continue;
+        }
+        entries[r] += dlen(x);
+        rows[r] += 1 + (h->parent[x] >= 0 && next[h->parent[x]] != x);  // Y write (+ parent read for a head)
+        if (next[x] < 0) longest[r] = std::max(longest[r], run[x]);
+    }
+    double us = 0.0;
+    if (seg_entries > 0)
+        us += kLaunchUs + std::max((double)split_len * kEntryUs, seg_entries * kRefRowBytes / (2.0 * kBytesPerUs));
+    for (int r = 1; r <= nrounds; ++r) {
+        if (entries[r] + rows[r] > 0)
+            us += kLaunchUs + std::max(longest[r] * kEntryUs, (entries[r] + rows[r]) * kRefRowBytes / kBytesPerUs);
+        if (comb[r] > 0) us += kLaunchUs + comb[r] * kRefRowBytes / kBytesPerUs;
+    }
+    if (fixup && h->square_self_loops) us += kLaunchUs;
+    return us;
+}
+
+// Modelled time of one product with every row stored in full (plain CSR on the same kernels).
+double Builder::csr_cost() const {
+    int64_t seg = 0, ent = 0, longest = 0;
+    for (int64_t x = 0; x < m; ++x) {
+        if (rlen(x) > split_min) {
+            seg += rlen(x);
+        } else {
+            ent += rlen(x) + 1;
+            longest = std::max(longest, rlen(x) + 1);
+        }
+    }
+    double us = kLaunchUs + std::max(longest * kEntryUs, ent * kRefRowBytes / kBytesPerUs);
+    if (seg > 0)
+        us += 2 * kLaunchUs + std::max((double)split_len * kEntryUs, seg * kRefRowBytes / (2.0 * kBytesPerUs));
+    return us;
+}
+
+// Write the entry stream and the work-item lists for the paths chosen by plan().
+cbm_status Builder::emit(int32_t nrounds) {
+    const int phases = (int)env_or("CBM_PHASES", kPhasesDefault);
+    const int64_t fine_min = env_or("CBM_FINE_MIN", kFineMinDefault);
     // rows that a row of ANOTHER work item is compressed against keep their unscaled sum in Y
     std::vector<uint8_t> internal(m, 0);
+    h->internal_rows.clear();
     for (int64_t x = 0; x < m; ++x) {
         const int64_t nc = cptr[x + 1] - cptr[x];
         internal[x] = nc > 1 || (nc == 1 && next[x] < 0);
         if (internal[x]) h->internal_rows.push_back((int32_t)x);
     }
-
     h->levels.assign(nrounds, CbmLevel{});
     h->tasks.clear();
     h->comb.clear();
     h->stream.clear();
     h->stream.reserve((size_t)(h->dptr[m] + m));
     h->num_slots = 0;
+    h->seg_deltas = 0;
     int64_t split_rows = 0;
     std::vector<std::vector<CbmTask>> rtasks(nrounds + 1), rcomb(nrounds + 1);
-    const int kPhases = std::getenv("CBM_PHASES") ? std::atoi(std::getenv("CBM_PHASES")) : kPhasesDefault;
-    const int64_t kFineMin = std::getenv("CBM_FINE_MIN") ? std::atol(std::getenv("CBM_FINE_MIN")) : kFineMinDefault;
-    std::vector<std::vector<CbmTask>> seg_tasks((size_t)CBM_XCD * (kPhases + 1));  // [xcd][phase]; last = unphased
-    h->seg_deltas = 0;
+    std::vector<std::vector<CbmTask>> seg_tasks((size_t)CBM_XCD * (phases + 1));  // [xcd][phase]; last = unphased
     for (int64_t i = 0; i < m; ++i) {
         const int32_t x = order[i];
         const int32_t y = h->parent[x];
@@ -465,6 +513,8 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
             // A long row is cut into segments that depend on nothing.  Its entries are re-sorted by column
             // and cut at the CBM_XCD column-range boundaries first: all segments of one column range run on
             // one XCD (workgroup id mod 8), so the popular rows of X in that range stay in that XCD's L2.
+            // Very long rows are cut finer still: each XCD's range is walked in `phases` sub-ranges, one after
+            // the other, so that at any time an XCD gathers from 1/(8 phases) of X.
             ++split_rows;
             const int64_t len = dlen(x);
             const int64_t base = (int64_t)h->stream.size();
@@ -473,19 +523,16 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
                 return (a & CBM_ENTRY_INDEX_MASK) < (b2 & CBM_ENTRY_INDEX_MASK);
             });
             const int64_t slot0 = h->num_slots;
-            // Very long rows are cut finer still: each XCD's column range is walked in kPhases sub-ranges, one
-            // after the other, so that at any time an XCD gathers from 1/(8 kPhases) of X and its 4 MiB L2
-            // holds a larger share of the popular rows.  Shorter split rows get one piece per XCD range.
-            const int fine = len >= kFineMin ? kPhases : 1;  // pieces per XCD range
+            const int fine = len >= fine_min ? phases : 1;  // pieces per XCD range
             const int npieces = CBM_XCD * fine;
             int64_t pos = 0;
             for (int f = 0; f < npieces; ++f) {
                 const uint32_t hi = (uint32_t)(((int64_t)(f + 1) * n + npieces - 1) / npieces);  // columns < hi
                 int64_t end = pos;
                 while (end < len && (h->stream[base + end] & CBM_ENTRY_INDEX_MASK) < hi) ++end;
-                auto& list = seg_tasks[(size_t)(f / fine) * (kPhases + 1) + (fine > 1 ? f % fine : kPhases)];
-                for (int64_t b = pos; b < end; b += kSplitLen) {
-                    const int64_t e = std::min(end, b + kSplitLen);
+                auto& list = seg_tasks[(size_t)(f / fine) * (phases + 1) + (fine > 1 ? f % fine : phases)];
+                for (int64_t b = pos; b < end; b += split_len) {
+                    const int64_t e = std::min(end, b + split_len);
                     list.push_back({(int32_t)h->num_slots, -1, (uint32_t)(base + b), (uint32_t)(e - b) | CBM_TASK_SEGMENT});
                     ++h->num_slots;
                 }
@@ -509,13 +556,14 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
         R.parent_reads += y >= 0;
     }
     if ((int64_t)h->stream.size() >= (int64_t)UINT32_MAX) return CBM_ERR_UNSUPPORTED;
+    // longest first: wave-mates get similar lengths and the tail of a launch is short
     auto longest_first = [](const CbmTask& a, const CbmTask& b2) {
         return (a.len_flags & CBM_TASK_LEN_MASK) > (b2.len_flags & CBM_TASK_LEN_MASK);
     };
     for (int j = 0; j < CBM_XCD; ++j) {  // segment work items first: one block per XCD, phases in order
         h->seg_begin[j] = (int64_t)h->tasks.size();
-        for (int ph = 0; ph <= kPhases; ++ph) {
-            auto& list = seg_tasks[(size_t)j * (kPhases + 1) + ph];
+        for (int ph = 0; ph <= phases; ++ph) {
+            auto& list = seg_tasks[(size_t)j * (phases + 1) + ph];
             std::stable_sort(list.begin(), list.end(), longest_first);
             h->tasks.insert(h->tasks.end(), list.begin(), list.end());
         }
@@ -524,7 +572,6 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     for (int r = 1; r <= nrounds; ++r) {
         CbmLevel& R = h->levels[r - 1];
         auto& lt = rtasks[r];
-        // longest first: wave-mates get similar lengths and the tail of the launch is short
         std::stable_sort(lt.begin(), lt.end(), longest_first);
         R.task_begin = (int64_t)h->tasks.size();
         R.task_count = (int64_t)lt.size();
@@ -533,33 +580,132 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
         R.comb_count = (int64_t)rcomb[r].size();
         h->comb.insert(h->comb.end(), rcomb[r].begin(), rcomb[r].end());
     }
+    h->stats.num_split_rows = split_rows;
+    return CBM_OK;
+}
 
-    lap("levels + work lists");
-    // ---- counters (Properties 1 and 2) -----------------------------------------------------------
+}  // namespace
+
+cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const int32_t* in_colidx, cbm_handle* h) {
+    auto t0 = std::chrono::steady_clock::now();
+    const cbm_build_opts& o = h->opts;
+    if (o.alpha < 0 || o.max_depth < -1 || o.hub_cap < -1 || o.max_candidates < -1 || o.num_threads < 0)
+        return CBM_ERR_INVALID_ARG;
+    if (m > (int64_t)CBM_ENTRY_INDEX_MASK || n > (int64_t)CBM_ENTRY_INDEX_MASK) return CBM_ERR_UNSUPPORTED;
+    if (o.add_self_loops && m != n) return CBM_ERR_INVALID_ARG;
+    Builder B;
+    B.h = h;
+    B.m = m;
+    B.n = n;
+    B.nthreads = o.num_threads > 0 ? o.num_threads : (int)std::max(1u, std::thread::hardware_concurrency());
+    B.alpha = o.alpha;
+    B.min_saving = std::max(o.alpha, 1);  // strict gain at alpha = 0: draws go to the virtual edge
+    B.auto_depth = o.max_depth == 0;
+    B.max_depth = o.max_depth == 0 ? kDefaultMaxDepth : o.max_depth;  // -1 = unlimited
+    B.hub_cap = o.hub_cap == 0 ? kDefaultHubCap : o.hub_cap;
+    B.max_cand = o.max_candidates == 0 ? kDefaultMaxCand : o.max_candidates;
+    B.verbose = std::getenv("CBM_VERBOSE") != nullptr;
+    B.last = t0;
+    B.split_len = env_or("CBM_SPLIT_LEN", kSplitLenDefault);
+    B.split_min = env_or("CBM_SPLIT_MIN", kSplitMinDefault);
+    h->m = m;
+    h->n = n;
+    h->eff_alpha = B.alpha;
+    h->eff_max_depth = B.max_depth;
+    h->eff_hub_cap = B.hub_cap;
+    h->eff_max_cand = B.max_cand;
+    h->square_self_loops = o.add_self_loops != 0;
+
+    cbm_status st = B.validate(in_rowptr, in_colidx);
+    if (st != CBM_OK) return st;
+    B.rowptr = in_rowptr;
+    B.colidx = in_colidx;
+    if (o.add_self_loops) B.self_loops(in_rowptr, in_colidx);
+    B.nnz = B.rowptr[m];
+    if (B.nnz >= (int64_t)UINT32_MAX) return CBM_ERR_UNSUPPORTED;
+    h->rownnz.resize(m);
+    for (int64_t i = 0; i < m; ++i) h->rownnz[i] = (int32_t)(B.rowptr[i + 1] - B.rowptr[i]);
+    B.lap("validate + A v I");
+
+    // a depth cap of 1 stores every row in full (plain CSR): no candidate search needed
+    if (B.max_depth != 1 && m > 1)
+        B.grow_tree();
+    else
+        B.all_roots();
+    B.delta_lists();
+
+    if (h->square_self_loops) {  // D^-1/2 of A v I
+        h->dinv.resize(m);
+        for (int64_t i = 0; i < m; ++i) h->dinv[i] = (float)(1.0 / std::sqrt((double)B.rlen(i)));
+    }
+
+    // ---- paths, rounds and GPU work lists ---------------------------------------------------------
+    // The tree is cut into vertical paths.  A path is ONE work item: its running sum stays in
+    // registers from row to row (c_x = c_y + deltas, Eq. (5)), so only the head of a path waits for
+    // another work item, the one that produced its parent's row.  Paths whose head hangs off a row of
+    // a round-r path run in round r + 1, and every round is one kernel launch.  Longer paths mean fewer
+    // rounds but a longer chain of dependent batches inside one work item; the length cap is the one
+    // the cost model likes best.  With the default depth option the model may also find that no tree
+    // pays for its extra launches (small graphs): then every row is stored in full.
+    B.tree_index();
+    int32_t nrounds = 0;
+    const int64_t forced_len = env_or("CBM_PATH_MAX", 0);
+    int64_t best_len = forced_len;
+    double best_us = 0.0;
+    if (best_len <= 0) {
+        best_us = 1e300;
+        for (int64_t cand : kPathChoices) {
+            int32_t nr = 0;
+            const double us = B.plan(cand, &nr);
+            if (B.verbose)
+                std::fprintf(stderr, "[cbm_build] path cap %4ld: %d rounds, model %.1f us\n", (long)cand, nr, us);
+            if (us < best_us) {
+                best_us = us;
+                best_len = cand;
+            }
+        }
+    }
+    if (B.auto_depth && forced_len <= 0 && B.max_depth != 1 && m > 1) {
+        const double csr_us = B.csr_cost();
+        if (B.verbose)
+            std::fprintf(stderr, "[cbm_build] all rows in full: model %.1f us (tree: %.1f us)\n", csr_us, best_us);
+        if (csr_us <= best_us) {
+            B.all_roots();
+            B.delta_lists();
+            B.tree_index();
+        }
+    }
+    B.plan(best_len, &nrounds);
     cbm_stats_t& s = h->stats;
     std::memset(&s, 0, sizeof(s));
+    st = B.emit(nrounds);
+    if (st != CBM_OK) return st;
+    B.lap("paths + work lists");
+
+    // ---- counters (Properties 1 and 2) -----------------------------------------------------------
     s.m = m;
     s.n = n;
-    s.nnz = nnz;
+    s.nnz = B.nnz;
+    int32_t depth = 0;
     for (int64_t x = 0; x < m; ++x) {
+        depth = std::max(depth, h->level[x]);
         s.num_delta_plus += h->nplus[x];
         s.num_delta_minus += h->nminus[x];
         if (h->parent[x] < 0) {
             ++s.num_roots;
-            s.scalar_ops += rlen(x);
+            s.scalar_ops += B.rlen(x);
         } else {
             s.scalar_ops += 1 + h->nplus[x] + h->nminus[x];
         }
     }
     s.num_internal = (int64_t)h->internal_rows.size();
     s.num_tasks = (int64_t)h->tasks.size();
-    s.num_split_rows = split_rows;
     s.bytes_csr = 8 * (m + 1) + 4 * in_rowptr[m];
     s.bytes_cbm = 4 * (int64_t)h->stream.size() + (int64_t)sizeof(CbmTask) * (int64_t)(h->tasks.size() + h->comb.size()) +
                   4 * (int64_t)h->internal_rows.size() + 4 * (int64_t)h->dinv.size();
     s.depth = depth;
     s.rounds = nrounds;
-    s.alpha = alpha;
+    s.alpha = B.alpha;
     s.add_self_loops = o.add_self_loops != 0;
     s.build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     return CBM_OK;

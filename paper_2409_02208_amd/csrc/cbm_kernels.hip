@@ -417,7 +417,8 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
         rec.kind = 1;
         rec.tasks = h->num_slots;
         rec.deltas = h->seg_deltas;
-        rec.algorithmic_bytes = h->seg_deltas * per_delta + h->num_slots * (rowb + (int64_t)sizeof(CbmTask));
+        // the method's bytes only: the partial sums of split rows are this implementation's overhead
+        rec.algorithmic_bytes = h->seg_deltas * per_delta;
         ProfScope ps(h, stream, rec);
         var.segments(ctx, CbmLevel{});
     }
@@ -430,9 +431,9 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
             rec.tasks = L.task_count;
             rec.deltas = L.deltas;
             // per delta: one X row + its entry (+ d^-1/2); per row: one Y write + its marker entry (+ d^-1/2);
-            // per work item: its 16-byte record and, if it has one, the parent's row
+            // per work item with a parent: the parent's row
             rec.algorithmic_bytes = L.deltas * per_delta + (L.rows_written + L.parent_reads) * rowb +
-                                    L.task_count * (int64_t)sizeof(CbmTask) + (mode != 0 ? 8 : 4) * L.rows_written;
+                                    (mode != 0 ? 8 : 4) * L.rows_written;
             ProfScope ps(h, stream, rec);
             var.level(ctx, L);
         }
@@ -441,8 +442,8 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
             rec.kind = 2;
             rec.level = (int32_t)l + 1;
             rec.tasks = L.comb_count;
-            rec.algorithmic_bytes = (L.comb_segments + L.comb_parent_reads + L.comb_count) * rowb +
-                                    L.comb_count * (int64_t)sizeof(CbmTask);
+            // split rows: the Y write and the parent read belong to the method, the partial sums do not
+            rec.algorithmic_bytes = (L.comb_parent_reads + L.comb_count) * rowb + (mode != 0 ? 8 : 4) * L.comb_count;
             ProfScope ps(h, stream, rec);
             var.combine(ctx, L);
         }
@@ -452,7 +453,7 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
         cbm_launch_record rec{};
         rec.kind = 3;
         rec.tasks = nr;
-        rec.algorithmic_bytes = nr * (2 * rowb + 8);
+        rec.algorithmic_bytes = 0;  // the deferred row scale is overhead of this implementation
         ProfScope ps(h, stream, rec);
         dim3 grid((unsigned)((nr + 3) / 4));
         if (mode == 1)

@@ -77,7 +77,7 @@ def test_invariants_random(alpha, self_loops):
     rows[4] = []
     rows[11] = list(rows[10])
     rowptr, colidx = _csr(rows)
-    h = cbm.cbm_build(m, n, rowptr, colidx, alpha=alpha, add_self_loops=self_loops, host_only=True)
+    h = cbm.cbm_build(m, n, rowptr, colidx, alpha=alpha, add_self_loops=self_loops, host_only=True, max_depth=16)
     _check_invariants(m, n, rowptr, colidx, h, alpha, self_loops)
     cbm.cbm_free(h)
 
@@ -108,8 +108,20 @@ def test_depth_cap_and_pruning_options():
         assert s["num_delta_plus"] + s["num_delta_minus"] >= full["num_delta_plus"] + full["num_delta_minus"]
     s1 = cbm.cbm_stats(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=1, host_only=True))
     assert s1["num_roots"] == g.n and s1["num_delta_plus"] == g.nnz and s1["num_delta_minus"] == 0  # plain CSR
-    s2 = cbm.cbm_stats(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=10 ** 6, host_only=True))
+    s2 = cbm.cbm_stats(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=10 ** 6, host_only=True, max_depth=16))
     assert s2["num_roots"] == g.n and s2["depth"] == 1
+
+
+def test_automatic_depth_uses_the_cost_model():
+    # default options: a tree only where it pays for its extra dependent launches
+    g = wl.tiny_graph()
+    s = cbm.cbm_stats(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, host_only=True))
+    assert s["depth"] == 1 and s["rounds"] == 1 and s["num_roots"] == g.n      # launch-bound: plain CSR
+    forced = cbm.cbm_stats(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=16, host_only=True))
+    assert forced["depth"] > 1 and forced["num_delta_plus"] + forced["num_delta_minus"] < s["num_delta_plus"]
+    g = wl.collaboration_graph(n=40000)
+    s = cbm.cbm_stats(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, host_only=True))
+    assert s["depth"] > 1 and s["scalar_ops"] < 0.7 * s["nnz"]                  # bandwidth-bound: the tree pays
 
 
 def test_special_shapes():
@@ -123,12 +135,12 @@ def test_special_shapes():
     # identical rows: one stored in full, the others cost one op each
     row = [1, 4, 5, 7]
     rowptr, colidx = _csr([row] * 9)
-    s = cbm.cbm_stats(cbm.cbm_build(9, 8, rowptr, colidx, host_only=True))
+    s = cbm.cbm_stats(cbm.cbm_build(9, 8, rowptr, colidx, host_only=True, max_depth=16))
     assert s["num_delta_plus"] == 4 and s["num_delta_minus"] == 0 and s["scalar_ops"] == 4 + 8
     # empty matrix, empty rows, single row, rectangular
     for rows, n in ([], 5), ([[]] * 3, 4), ([[0, 2]], 3), ([[0, 1, 2, 3, 4, 5, 6], [0, 1, 2, 3, 4, 5]], 7):
         rowptr, colidx = _csr(rows)
-        h = cbm.cbm_build(len(rows), n, rowptr, colidx, host_only=True)
+        h = cbm.cbm_build(len(rows), n, rowptr, colidx, host_only=True, max_depth=16)
         _check_invariants(len(rows), n, rowptr, colidx, h, 0, False)
 
 
@@ -138,7 +150,7 @@ def test_long_rows_are_split_into_segments():
     for size, pieces in ((900, 8), (1800, 32)):  # one piece per XCD column range; 4 sub-ranges each from 1024 entries
         rows = [sorted(rng.choice(n, size=size, replace=False).tolist()), [1, 2, 3], []]
         rowptr, colidx = _csr(rows)
-        h = cbm.cbm_build(3, n, rowptr, colidx, host_only=True)
+        h = cbm.cbm_build(3, n, rowptr, colidx, host_only=True, max_depth=16)
         s = _check_invariants(3, n, rowptr, colidx, h, 0, False)
         assert s["num_split_rows"] == 1 and s["num_tasks"] == 2 + pieces
 
@@ -146,23 +158,23 @@ def test_long_rows_are_split_into_segments():
 def test_error_paths_return_status_codes():
     rowptr, colidx = _csr([[0, 1], [1]])
     with pytest.raises(cbm.CbmError) as e:
-        cbm.cbm_build(2, 2, np.array([0, 2, 1], dtype=np.int64), colidx, host_only=True)
+        cbm.cbm_build(2, 2, np.array([0, 2, 1], dtype=np.int64), colidx, host_only=True, max_depth=16)
     assert e.value.status == 2
     for bad in ([1, 0, 1], [0, 0, 1], [0, 5, 1], [-1, 1, 1]):
         with pytest.raises(cbm.CbmError) as e:
-            cbm.cbm_build(2, 2, rowptr, np.array(bad, dtype=np.int32), host_only=True)
+            cbm.cbm_build(2, 2, rowptr, np.array(bad, dtype=np.int32), host_only=True, max_depth=16)
         assert e.value.status == 2
     with pytest.raises(cbm.CbmError) as e:
-        cbm.cbm_build(2, 2, rowptr, colidx, alpha=-1, host_only=True)
+        cbm.cbm_build(2, 2, rowptr, colidx, alpha=-1, host_only=True, max_depth=16)
     assert e.value.status == 1
     with pytest.raises(cbm.CbmError) as e:  # self-loops need a square matrix
-        cbm.cbm_build(2, 3, rowptr, colidx, add_self_loops=True, host_only=True)
+        cbm.cbm_build(2, 3, rowptr, colidx, add_self_loops=True, host_only=True, max_depth=16)
     assert e.value.status == 1
     lib = ctypes.CDLL(cbm.LIB_PATH)
     assert lib.cbm_build(ctypes.c_int64(2), ctypes.c_int64(2), None, None, None, None) == 1
     lib.cbm_free(None)  # NULL-safe
     # a host-only handle refuses products (no device arrays) instead of computing anything on the CPU
-    h = cbm.cbm_build(2, 2, rowptr, colidx, host_only=True)
+    h = cbm.cbm_build(2, 2, rowptr, colidx, host_only=True, max_depth=16)
     lib.cbm_spmm.argtypes = [ctypes.c_void_p] * 2 + [ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64,
                                                      ctypes.c_void_p]
     assert lib.cbm_spmm(h.ptr, 16, 4, 4, 32, 4, None) == 6
@@ -174,7 +186,7 @@ def test_error_paths_return_status_codes():
                                      ("protein", dict(n=1200, knn=20)), ("rmat", dict(scale=10, edge_factor=8))])
 def test_invariants_on_reduced_workloads(name, kw):
     g = wl.make_graph(name, **kw)
-    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=1, host_only=True)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=1, host_only=True, max_depth=16)
     s = cbm.cbm_stats(h)
     rp, ci = cbm.cbm_decompress(h)
     # A v I rebuilt exactly

@@ -1,0 +1,86 @@
+"""GPU parity at the full sizes of the five configurations, in the launch
+configuration bench.py times (alpha and depth defaults, k of the config):
+sampled output rows against the oracle, and two properties that hold for
+every row at any size."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import cbm_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+FULL = {  # name -> (k values, alpha): as in bench.py
+    "tiny": ([16], 0),
+    "citation": ([500, 64, 3], 2),
+    "collaboration": ([128], 2),
+    "protein": ([256, 112], 2),
+    "rmat": ([128, 64], 2),
+}
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+
+    import paper_2409_02208_amd as cbm
+
+    assert torch.cuda.is_available()
+    return torch, cbm
+
+
+@pytest.mark.parametrize("name", wl.CONFIGS)
+def test_full_size_products(env, name):
+    torch, cbm = env
+    ks, alpha = FULL[name]
+    g = wl.make_graph(name)
+    print(f"{name}: n={g.n} nnz={g.nnz}", flush=True)
+    rng = np.random.default_rng(11)
+    rows = np.sort(rng.choice(g.n, size=min(g.n, 300), replace=False))
+    heavy = np.argsort(np.diff(g.rowptr))[-8:]  # the longest rows too: split rows, many segments
+    rows = np.unique(np.concatenate((rows, heavy)))
+    rows_t = torch.as_tensor(rows, device="cuda")
+    d = np.diff(g.rowptr) + 1
+
+    hn = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha)
+    s = cbm.cbm_stats(hn)
+    assert s["num_delta_plus"] + s["num_delta_minus"] <= s["nnz"] and s["scalar_ops"] <= s["nnz"]
+    for k in ks:
+        X = wl.gaussian_features(g.n, k, g.meta["seed"])
+        Xd = torch.from_numpy(X).cuda()
+        Y = torch.full((g.n, k), float("nan"), device="cuda")
+        cbm.cbm_spmm_normalized(hn, Xd, Y)
+        torch.cuda.synchronize()
+        assert not bool(torch.isnan(Y).any()), "every row of Y must be written"
+        ref = orc.spmm_csr_normalized(g.rowptr, g.colidx, X, rows=rows, d=d)
+        got = Y[rows_t].cpu().numpy().astype(np.float64)
+        err = np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)
+        assert err.max() <= 1e-5, (name, k, float(err.max()))
+        del Xd, Y
+
+    # property at any size: A_hat (D^1/2 1) = D^1/2 1, for every row
+    k = 8
+    v = np.sqrt(d.astype(np.float64)).astype(np.float32)
+    Xd = torch.from_numpy(np.repeat(v[:, None], k, axis=1).copy()).cuda()
+    Y = torch.empty((g.n, k), device="cuda")
+    cbm.cbm_spmm_normalized(hn, Xd, Y)
+    torch.cuda.synchronize()
+    rel = ((Y - Xd).abs() / Xd).max().item()
+    assert rel <= 1e-5, (name, rel)
+    cbm.cbm_free(hn)
+
+    # A.X on integer features: sampled rows bit-exact, and the column sums of Y equal deg^T X exactly
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=alpha)
+    k = 16
+    X = wl.integer_features(g.n, k, g.meta["seed"], lo=-2, hi=2)
+    Xd = torch.from_numpy(X).cuda()
+    Y = torch.full((g.n, k), float("nan"), device="cuda")
+    cbm.cbm_spmm(h, Xd, Y)
+    torch.cuda.synchronize()
+    ref = orc.spmm_csr(g.rowptr, g.colidx, X, rows=rows)
+    assert np.abs(ref).max() < 2 ** 24
+    assert np.array_equal(Y[rows_t].cpu().numpy().astype(np.float64), ref)
+    colsum = Y.double().sum(dim=0).cpu().numpy()            # 1^T (A X) = (A^T 1)^T X = deg^T X  (A symmetric)
+    want = (np.diff(g.rowptr).astype(np.float64)[:, None] * X.astype(np.float64)).sum(axis=0)
+    assert np.array_equal(colsum, want)
+    cbm.cbm_free(h)

@@ -70,7 +70,7 @@ def test_spmm_integer_features_bit_exact(env, graphs, name, k):
     torch, cbm = env
     g = graphs[name]
     X = wl.integer_features(g.n, k, g.meta["seed"])
-    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=16)
     got = _run(env, "cbm_spmm", h, X, g.n)
     ref = orc.spmm_csr(g.rowptr, g.colidx, X)
     assert np.abs(ref).max() < 2 ** 24
@@ -85,7 +85,7 @@ def test_spmm_normalized_gaussian(env, graphs, name, k):
     torch, cbm = env
     g = graphs[name]
     X = wl.gaussian_features(g.n, k, g.meta["seed"])
-    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=16)
     got = _run(env, "cbm_spmm_normalized", h, X, g.n)
     ref = orc.spmm_csr_normalized(g.rowptr, g.colidx, X)
     assert row_scaled_error(got, ref) <= TOL
@@ -124,7 +124,7 @@ def test_regular_graph_normalized_bit_exact(env):
         adj[v].add(u)
     rowptr, colidx = _csr(adj)
     X = wl.integer_features(n, 64, 3)
-    h = cbm.cbm_build(n, n, rowptr, colidx, add_self_loops=True)
+    h = cbm.cbm_build(n, n, rowptr, colidx, add_self_loops=True, max_depth=16)
     got = _run(env, "cbm_spmm_normalized", h, X, n)
     assert np.array_equal(got.astype(np.float64), orc.spmm_csr_normalized(rowptr, colidx, X))
 
@@ -138,7 +138,8 @@ def test_lower_triangular_chain_is_cumsum(env):
     for depth in (-1, 0, 4):
         h = cbm.cbm_build(m, m, rowptr, colidx, max_depth=depth)
         s = cbm.cbm_stats(h)
-        assert s["depth"] == (m if depth == -1 else 16 if depth == 0 else 4)
+        # 0 = automatic: cap 16, or every row in full when the cost model finds the tree does not pay
+        assert s["depth"] in ((m,) if depth == -1 else (1, 16) if depth == 0 else (4,))
         assert np.array_equal(_run(env, "cbm_spmm", h, X, m).astype(np.float64), want)
 
 
@@ -153,12 +154,12 @@ def test_split_rows_and_empty_rows(env):
     rowptr, colidx = _csr(rows)
     for k in (4, 100, 256):
         X = wl.integer_features(n, k, 2)
-        h = cbm.cbm_build(n, n, rowptr, colidx)
+        h = cbm.cbm_build(n, n, rowptr, colidx, max_depth=16)
         s = cbm.cbm_stats(h)
         assert s["num_split_rows"] >= 2
         assert np.array_equal(_run(env, "cbm_spmm", h, X, n).astype(np.float64), orc.spmm_csr(rowptr, colidx, X))
         Xg = wl.gaussian_features(n, k, 2)
-        h = cbm.cbm_build(n, n, rowptr, colidx, add_self_loops=True)
+        h = cbm.cbm_build(n, n, rowptr, colidx, add_self_loops=True, max_depth=16)
         assert row_scaled_error(_run(env, "cbm_spmm_normalized", h, Xg, n),
                                 orc.spmm_csr_normalized(rowptr, colidx, Xg)) <= TOL
 
@@ -166,13 +167,13 @@ def test_split_rows_and_empty_rows(env):
 def test_degenerate_shapes(env):
     torch, cbm = env
     # empty matrix
-    h = cbm.cbm_build(0, 5, np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32))
+    h = cbm.cbm_build(0, 5, np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32), max_depth=16)
     X = torch.ones((5, 4), device="cuda")
     Y = torch.empty((0, 4), device="cuda")
     cbm.cbm_spmm(h, X, Y)
     # all rows empty: Y must be written with zeros
     rowptr, colidx = _csr([[]] * 7)
-    h = cbm.cbm_build(7, 5, rowptr, colidx)
+    h = cbm.cbm_build(7, 5, rowptr, colidx, max_depth=16)
     got = _run(env, "cbm_spmm", h, np.ones((5, 4), dtype=np.float32), 7)
     assert np.array_equal(got, np.zeros((7, 4), dtype=np.float32))
     # rectangular, k = 1 (the matrix-vector product of Eq. (6)), single row
@@ -180,15 +181,15 @@ def test_degenerate_shapes(env):
     rows = [sorted(np.flatnonzero(rng.random(37) < 0.3).tolist()) for _ in range(90)]
     rowptr, colidx = _csr(rows)
     X = wl.integer_features(37, 1, 0)
-    h = cbm.cbm_build(90, 37, rowptr, colidx)
+    h = cbm.cbm_build(90, 37, rowptr, colidx, max_depth=16)
     assert np.array_equal(_run(env, "cbm_spmm", h, X, 90).astype(np.float64), orc.spmm_csr(rowptr, colidx, X))
     rowptr, colidx = _csr([[0, 2]])
-    h = cbm.cbm_build(1, 3, rowptr, colidx)
+    h = cbm.cbm_build(1, 3, rowptr, colidx, max_depth=16)
     X = np.array([[1, 2], [3, 4], [5, 6]], dtype=np.float32)
     assert np.array_equal(_run(env, "cbm_spmm", h, X, 1), np.array([[6, 8]], dtype=np.float32))
     # isolated node in the normalised product: A v I row is {x}, d = 1, output = input row
     rowptr, colidx = _csr([[1], [0], []])
-    h = cbm.cbm_build(3, 3, rowptr, colidx, add_self_loops=True)
+    h = cbm.cbm_build(3, 3, rowptr, colidx, add_self_loops=True, max_depth=16)
     X = np.array([[2.0, 4.0], [6.0, 8.0], [3.0, 5.0]], dtype=np.float32)
     got = _run(env, "cbm_spmm_normalized", h, X, 3)
     np.testing.assert_allclose(got, [[4.0, 6.0], [4.0, 6.0], [3.0, 5.0]], rtol=1e-6)
@@ -197,7 +198,7 @@ def test_degenerate_shapes(env):
 def test_strided_and_misaligned_operands(env, graphs):
     torch, cbm = env
     g = graphs["collaboration"]
-    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=16)
     k = 48
     X = wl.integer_features(g.n, k, 9)
     ref = orc.spmm_csr(g.rowptr, g.colidx, X)
@@ -220,7 +221,7 @@ def test_strided_and_misaligned_operands(env, graphs):
 def test_argument_errors_on_device_handle(env, graphs):
     torch, cbm = env
     g = graphs["tiny"]
-    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx)  # no self-loops
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=16)  # no self-loops
     X = torch.zeros((g.n, 8), device="cuda")
     Y = torch.zeros((g.n, 8), device="cuda")
     with pytest.raises(cbm.CbmError) as e:
@@ -258,7 +259,7 @@ def test_gcn2_forward(env, graphs, name, f_in, hidden, f_out):
     X = wl.gaussian_features(g.n, f_in, seed)
     W0 = wl.glorot_uniform(f_in, hidden, seed)
     W1 = wl.glorot_uniform(hidden, f_out, seed)
-    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=16)
     ws = torch.empty(cbm.cbm_gcn2_workspace_bytes(h, f_in, hidden, f_out), dtype=torch.uint8, device="cuda")
     out = torch.full((g.n, f_out), float("nan"), device="cuda")
     cbm.cbm_gcn2_forward(h, *(torch.from_numpy(a).cuda() for a in (X, W0, W1)), out, ws)
@@ -271,7 +272,7 @@ def test_iterated_products_ping_pong(env, graphs):
     # X_{t+1} = A X_t, ten times; each iterate is checked against the oracle fed the GPU's previous iterate
     torch, cbm = env
     g = graphs["collaboration"]
-    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=1)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=1, max_depth=16)
     cur = torch.from_numpy(wl.gaussian_features(g.n, 32, 4)).cuda()
     nxt = torch.empty_like(cur)
     for _ in range(10):
@@ -286,7 +287,7 @@ def test_iterated_products_ping_pong(env, graphs):
 def test_profile_records(env, graphs):
     torch, cbm = env
     g = graphs["protein"]
-    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=16)
     s = cbm.cbm_stats(h)
     cbm.cbm_profile_enable(h, True)
     X = torch.from_numpy(wl.gaussian_features(g.n, 64, 1)).cuda()
