@@ -306,6 +306,8 @@ def main():
     ap.add_argument("--no-gcn", action="store_true", help="skip the GCN inference timing")
     ap.add_argument("--no-csr", action="store_true", help="skip the all-roots (GPU CSR) comparison")
     ap.add_argument("--report", default="", help="walk all five graphs and write a markdown table to this file")
+    ap.add_argument("--probe-gemm", action="store_true",
+                    help="only time cbm_dense_matmul on the X.W shapes of the GCN configurations (for rocprofv3 counters)")
     ap.add_argument("--probe-copy", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times (calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -328,6 +330,19 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"probe": "copy", "bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4}))
+        return
+    if args.probe_gemm:
+        res = []
+        for M, N, K in ((132534, 256, 256), (132534, 112, 256), (19717, 64, 500), (19717, 3, 64)):
+            A = torch.randn(M, K, device="cuda")
+            B = torch.randn(K, N, device="cuda")
+            C = torch.empty(M, N, device="cuda")
+            ms = time_steps(torch, lambda: cbm.cbm_dense_matmul(A, B, C), args.steps, args.warmup)
+            res.append(dict(M=M, N=N, K=K, ms=ms, tflops=2.0 * M * N * K / ms / 1e9,
+                            frac_of_fp32_mfma_peak=2.0 * M * N * K / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS,
+                            GBps=4.0 * (M * K + K * N + M * N) / ms / 1e6))
+            log(f"matmul {M}x{K} . {K}x{N}: {ms:.4f} ms, {res[-1]['tflops']:.1f} TFLOP/s")
+        print(json.dumps({"probe": "gemm", "dtype": "f32", "peak_tflops": FP32_MFMA_PEAK_TFLOPS, "shapes": res}))
         return
     if args.report:
         return report(args, torch, cbm, wl, orc, csr_ref)
