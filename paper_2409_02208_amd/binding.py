@@ -59,6 +59,10 @@ def _lib():
     if _LIB is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2409_02208_amd.build`")
+        # PyTorch ships its own HIP runtime.  It must be in the process before libcbm.so is loaded, so that
+        # the library binds to that same runtime: device pointers and streams are only meaningful within one.
+        import torch  # noqa: F401
+
         lib = C.CDLL(LIB_PATH)
         vp, i64, i32, f32p = C.c_void_p, C.c_int64, C.c_int32, C.c_void_p
         lib.cbm_build.argtypes = [i64, i64, vp, vp, C.POINTER(cbm_build_opts), C.POINTER(vp)]
