@@ -68,6 +68,11 @@ typedef enum {
  * max_candidates Candidate parents kept per row.  0 = default (8); -1 = keep all
  *                (with hub_cap = -1, max_depth = -1 and alpha = 0 the tree is then
  *                a true minimum spanning tree of the extended distance graph).
+ * seed_roots     Rows forced to be stored in full before the tree is grown, spread
+ *                evenly over the row range.  With a depth cap, growing from many
+ *                seeds at once gives wider levels (more parallel work per dependent
+ *                launch) and often fewer deltas.  0 = automatic (the cost model
+ *                picks among 0, m/128, m/32, m/8); -1 = none; > 0 = that many.
  * num_threads    Host threads for the build.  0 = all hardware threads.
  * device         HIP device that will own the arrays.  -1 = current device.
  */
@@ -77,6 +82,7 @@ typedef struct {
     int32_t max_depth;
     int32_t hub_cap;
     int32_t max_candidates;
+    int32_t seed_roots;
     int32_t num_threads;
     int32_t device;
     uint32_t flags;

@@ -31,7 +31,8 @@ class CbmError(RuntimeError):
 
 class cbm_build_opts(C.Structure):
     _fields_ = [("alpha", C.c_int32), ("add_self_loops", C.c_int32), ("max_depth", C.c_int32),
-                ("hub_cap", C.c_int32), ("max_candidates", C.c_int32), ("num_threads", C.c_int32),
+                ("hub_cap", C.c_int32), ("max_candidates", C.c_int32), ("seed_roots", C.c_int32),
+                ("num_threads", C.c_int32),
                 ("device", C.c_int32), ("flags", C.c_uint32)]
 
 
@@ -127,14 +128,14 @@ class Handle:
 
 def cbm_build(m: int, n: int, rowptr: np.ndarray, colidx: np.ndarray, *, alpha: int = 0,
               add_self_loops: bool = False, max_depth: int = 0, hub_cap: int = 0, max_candidates: int = 0,
-              num_threads: int = 0, device: int = -1, host_only: bool = False) -> Handle:
+              seed_roots: int = 0, num_threads: int = 0, device: int = -1, host_only: bool = False) -> Handle:
     rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
     colidx = np.ascontiguousarray(colidx, dtype=np.int32)
     if rowptr.shape != (m + 1,):
         raise ValueError("rowptr must have m + 1 entries")
     if len(colidx) < int(rowptr[-1]):
         raise ValueError("colidx shorter than rowptr[m]")
-    opts = cbm_build_opts(alpha, int(add_self_loops), max_depth, hub_cap, max_candidates, num_threads, device,
+    opts = cbm_build_opts(alpha, int(add_self_loops), max_depth, hub_cap, max_candidates, seed_roots, num_threads, device,
                           CBM_FLAG_HOST_ONLY if host_only else 0)
     out = C.c_void_p()
     _check(_lib().cbm_build(m, n, rowptr.ctypes.data, colidx.ctypes.data, C.byref(opts), C.byref(out)), "cbm_build")

@@ -136,7 +136,10 @@ struct Builder {
 
     cbm_status validate(const int64_t* in_rowptr, const int32_t* in_colidx);
     void self_loops(const int64_t* in_rowptr, const int32_t* in_colidx);
-    void grow_tree();
+    std::vector<int64_t> optr;  // candidate edges bucketed by parent
+    std::vector<int32_t> ochild, ow;
+    void find_candidates();
+    void prim(int64_t seeds);
     void all_roots();
     void delta_lists();
     // paths
@@ -198,10 +201,12 @@ void Builder::self_loops(const int64_t* in_rowptr, const int32_t* in_colidx) {
 void Builder::all_roots() {
     h->parent.assign(m, -1);
     h->level.assign(m, 1);
+    h->dptr.assign(m + 1, 0);
+    for (int64_t x = 0; x < m; ++x) h->dptr[x + 1] = h->dptr[x] + rlen(x);
 }
 
-// Candidate parents from shared columns, then Prim growth from the virtual vertex with a depth cap.
-void Builder::grow_tree() {
+// Candidate parents: for every row, the rows that share columns with it, ranked by exact Hamming distance.
+void Builder::find_candidates() {
     // transpose: rows holding each column
     std::vector<int64_t> tptr(n + 1, 0);
     std::vector<int32_t> trow(nnz);
@@ -288,11 +293,12 @@ void Builder::grow_tree() {
     lap("candidates");
 
     // bucket candidate edges by parent: Prim pushes the out-edges of each newly attached row
-    std::vector<int64_t> optr(m + 1, 0);
+    optr.assign(m + 1, 0);
     for (auto& v : cand_per_thread)
         for (auto& c : v) ++optr[c.parent + 1];
     for (int64_t i = 0; i < m; ++i) optr[i + 1] += optr[i];
-    std::vector<int32_t> ochild(optr[m]), ow(optr[m]);
+    ochild.resize(optr[m]);
+    ow.resize(optr[m]);
     {
         std::vector<int64_t> fill(optr.begin(), optr.end() - 1);
         for (auto& v : cand_per_thread) {
@@ -304,11 +310,22 @@ void Builder::grow_tree() {
             std::vector<Cand>().swap(v);
         }
     }
+}
+
+// Prim growth from the virtual vertex over the candidate edges, depth-capped.  `seeds` rows, evenly
+// spread over the index range, are forced to be stored in full before anything else is attached:
+// with a depth cap, growing from many seeds at once gives wider levels (more parallel work per
+// dependent launch) and often fewer deltas than growing from the few cheapest rows only.
+// Also leaves in dptr[] the delta count of every row (the weight of its tree edge).
+void Builder::prim(int64_t seeds) {
     h->parent.assign(m, -1);
     h->level.assign(m, 0);
+    std::vector<int32_t> wsel(m, 0);
     std::vector<HeapEdge> init;
     init.reserve(m);
     for (int64_t x = 0; x < m; ++x) init.push_back({(uint64_t)rlen(x) << 1, (int32_t)x, -1});
+    if (seeds > 0 && seeds < m)
+        for (int64_t i = 0; i < seeds; ++i) init[(size_t)(i * m / seeds)].key = 0;  // popped before any other edge
     std::priority_queue<HeapEdge, std::vector<HeapEdge>, std::greater<HeapEdge>> pq(std::greater<HeapEdge>(),
                                                                                     std::move(init));
     while (!pq.empty()) {
@@ -318,11 +335,13 @@ void Builder::grow_tree() {
         int32_t lvl = e.y < 0 ? 1 : h->level[e.y] + 1;
         h->parent[e.x] = e.y;
         h->level[e.x] = lvl;
+        wsel[e.x] = e.y < 0 ? (int32_t)rlen(e.x) : (int32_t)(e.key >> 1);
         if (max_depth > 0 && lvl >= max_depth) continue;  // nothing may hang below the cap
         for (int64_t p = optr[e.x]; p < optr[e.x + 1]; ++p)
             if (h->level[ochild[p]] == 0) pq.push({((uint64_t)ow[p] << 1) | 1u, ochild[p], e.x});
     }
-    lap("tree");
+    h->dptr.assign(m + 1, 0);
+    for (int64_t x = 0; x < m; ++x) h->dptr[x + 1] = h->dptr[x] + wsel[x];
 }
 
 // Delta lists (Eq. (2)) of every tree edge by list merge.
@@ -589,7 +608,8 @@ cbm_status Builder::emit(int32_t nrounds) {
 cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const int32_t* in_colidx, cbm_handle* h) {
     auto t0 = std::chrono::steady_clock::now();
     const cbm_build_opts& o = h->opts;
-    if (o.alpha < 0 || o.max_depth < -1 || o.hub_cap < -1 || o.max_candidates < -1 || o.num_threads < 0)
+    if (o.alpha < 0 || o.max_depth < -1 || o.hub_cap < -1 || o.max_candidates < -1 || o.seed_roots < -1 ||
+        o.num_threads < 0)
         return CBM_ERR_INVALID_ARG;
     if (m > (int64_t)CBM_ENTRY_INDEX_MASK || n > (int64_t)CBM_ENTRY_INDEX_MASK) return CBM_ERR_UNSUPPORTED;
     if (o.add_self_loops && m != n) return CBM_ERR_INVALID_ARG;
@@ -627,54 +647,66 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     for (int64_t i = 0; i < m; ++i) h->rownnz[i] = (int32_t)(B.rowptr[i + 1] - B.rowptr[i]);
     B.lap("validate + A v I");
 
-    // a depth cap of 1 stores every row in full (plain CSR): no candidate search needed
-    if (B.max_depth != 1 && m > 1)
-        B.grow_tree();
-    else
-        B.all_roots();
-    B.delta_lists();
-
     if (h->square_self_loops) {  // D^-1/2 of A v I
         h->dinv.resize(m);
         for (int64_t i = 0; i < m; ++i) h->dinv[i] = (float)(1.0 / std::sqrt((double)B.rlen(i)));
     }
 
-    // ---- paths, rounds and GPU work lists ---------------------------------------------------------
+    // ---- tree, paths, rounds ---------------------------------------------------------------------
     // The tree is cut into vertical paths.  A path is ONE work item: its running sum stays in
     // registers from row to row (c_x = c_y + deltas, Eq. (5)), so only the head of a path waits for
     // another work item, the one that produced its parent's row.  Paths whose head hangs off a row of
     // a round-r path run in round r + 1, and every round is one kernel launch.  Longer paths mean fewer
-    // rounds but a longer chain of dependent batches inside one work item; the length cap is the one
-    // the cost model likes best.  With the default depth option the model may also find that no tree
-    // pays for its extra launches (small graphs): then every row is stored in full.
-    B.tree_index();
+    // rounds but a longer chain of dependent batches inside one work item.  The number of seeded roots
+    // and the path length cap are the pair the cost model likes best; with the default depth option the
+    // model may also find that no tree pays for its extra launches (small graphs): then every row is
+    // stored in full.  A depth cap of 1 means exactly that and needs no candidate search.
     int32_t nrounds = 0;
-    const int64_t forced_len = env_or("CBM_PATH_MAX", 0);
-    int64_t best_len = forced_len;
-    double best_us = 0.0;
-    if (best_len <= 0) {
-        best_us = 1e300;
-        for (int64_t cand : kPathChoices) {
-            int32_t nr = 0;
-            const double us = B.plan(cand, &nr);
-            if (B.verbose)
-                std::fprintf(stderr, "[cbm_build] path cap %4ld: %d rounds, model %.1f us\n", (long)cand, nr, us);
-            if (us < best_us) {
-                best_us = us;
-                best_len = cand;
-            }
-        }
-    }
-    if (B.auto_depth && forced_len <= 0 && B.max_depth != 1 && m > 1) {
-        const double csr_us = B.csr_cost();
-        if (B.verbose)
-            std::fprintf(stderr, "[cbm_build] all rows in full: model %.1f us (tree: %.1f us)\n", csr_us, best_us);
-        if (csr_us <= best_us) {
-            B.all_roots();
-            B.delta_lists();
+    int64_t best_len = kPathChoices[0], best_seeds = 0;
+    bool tree = B.max_depth != 1 && m > 1;
+    if (tree) {
+        B.find_candidates();
+        const int64_t forced_len = env_or("CBM_PATH_MAX", 0);
+        const int64_t forced_seeds = o.seed_roots > 0 ? o.seed_roots : o.seed_roots < 0 ? 0 : env_or("CBM_SEED_ROOTS", -1);
+        double best_us = 1e300;
+        for (int64_t seeds : {(int64_t)0, m / 128, m / 32, m / 8}) {
+            if (forced_seeds >= 0) seeds = forced_seeds;
+            B.prim(seeds);
             B.tree_index();
+            for (int64_t cap : kPathChoices) {
+                if (forced_len > 0) cap = forced_len;
+                int32_t nr = 0;
+                const double us = B.plan(cap, &nr);
+                if (B.verbose)
+                    std::fprintf(stderr, "[cbm_build] seeds %7ld path cap %4ld: %3d rounds, %ld deltas, model %.1f us\n",
+                                 (long)seeds, (long)cap, nr, (long)h->dptr[m], us);
+                if (us < best_us) {
+                    best_us = us;
+                    best_len = cap;
+                    best_seeds = seeds;
+                }
+                if (forced_len > 0) break;
+            }
+            if (forced_seeds >= 0 || m < 1024) break;
         }
+        if (B.auto_depth && forced_len <= 0) {
+            B.all_roots();
+            const double csr_us = B.csr_cost();
+            if (B.verbose)
+                std::fprintf(stderr, "[cbm_build] all rows in full: model %.1f us (best tree: %.1f us)\n", csr_us, best_us);
+            tree = best_us < csr_us;
+        }
+        B.lap("tree + path model");
     }
+    if (tree)
+        B.prim(best_seeds);
+    else
+        B.all_roots();
+    std::vector<int64_t>().swap(B.optr);
+    std::vector<int32_t>().swap(B.ochild);
+    std::vector<int32_t>().swap(B.ow);
+    B.delta_lists();
+    B.tree_index();
     B.plan(best_len, &nrounds);
     cbm_stats_t& s = h->stats;
     std::memset(&s, 0, sizeof(s));

@@ -100,9 +100,9 @@ def test_exact_mode_reaches_the_minimum_spanning_tree_weight(seed):
 
 def test_depth_cap_and_pruning_options():
     g = wl.tiny_graph()
-    full = cbm.cbm_stats(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=-1, host_only=True))
+    full = cbm.cbm_stats(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=-1, seed_roots=-1, host_only=True))
     for cap in (1, 2, 5):
-        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=cap, host_only=True)
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=cap, seed_roots=-1, host_only=True)
         s = _check_invariants(g.n, g.n, g.rowptr, g.colidx, h, 0, False)
         assert s["depth"] <= cap
         assert s["num_delta_plus"] + s["num_delta_minus"] >= full["num_delta_plus"] + full["num_delta_minus"]
@@ -122,6 +122,16 @@ def test_automatic_depth_uses_the_cost_model():
     g = wl.collaboration_graph(n=40000)
     s = cbm.cbm_stats(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, host_only=True))
     assert s["depth"] > 1 and s["scalar_ops"] < 0.7 * s["nnz"]                  # bandwidth-bound: the tree pays
+
+
+def test_seeded_roots():
+    g = wl.protein_graph(n=3000, knn=40)
+    for seeds in (-1, 0, 200):
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=8, seed_roots=seeds, host_only=True)
+        s = _check_invariants(g.n, g.n, g.rowptr, g.colidx, h, 0, True)
+        if seeds > 0:
+            t = cbm.cbm_get_tree(h)
+            assert s["num_roots"] >= seeds and all(t["parent"][i * g.n // seeds] < 0 for i in range(seeds))
 
 
 def test_special_shapes():
