@@ -662,7 +662,11 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     // model may also find that no tree pays for its extra launches (small graphs): then every row is
     // stored in full.  A depth cap of 1 means exactly that and needs no candidate search.
     int32_t nrounds = 0;
-    int64_t best_len = kPathChoices[0], best_seeds = 0;
+    int64_t best_len = kPathChoices[0], best_seeds = 0, best_split = B.split_min;
+    // rows longer than the split threshold are cut into per-XCD segments: worth a launch or two of their own on
+    // graphs with many long rows, a loss where only a handful exist
+    std::vector<int64_t> split_choices = {kSplitMinDefault, kSplitLenDefault};
+    if (std::getenv("CBM_SPLIT_MIN")) split_choices = {B.split_min};
     bool tree = B.max_depth != 1 && m > 1;
     if (tree) {
         B.find_candidates();
@@ -672,32 +676,57 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
         for (int64_t seeds : {(int64_t)0, m / 128, m / 32, m / 8}) {
             if (forced_seeds >= 0) seeds = forced_seeds;
             B.prim(seeds);
-            B.tree_index();
-            for (int64_t cap : kPathChoices) {
-                if (forced_len > 0) cap = forced_len;
-                int32_t nr = 0;
-                const double us = B.plan(cap, &nr);
-                if (B.verbose)
-                    std::fprintf(stderr, "[cbm_build] seeds %7ld path cap %4ld: %3d rounds, %ld deltas, model %.1f us\n",
-                                 (long)seeds, (long)cap, nr, (long)h->dptr[m], us);
-                if (us < best_us) {
-                    best_us = us;
-                    best_len = cap;
-                    best_seeds = seeds;
+            for (int64_t split : split_choices) {
+                B.split_min = split;
+                B.tree_index();
+                for (int64_t cap : kPathChoices) {
+                    if (forced_len > 0) cap = forced_len;
+                    int32_t nr = 0;
+                    const double us = B.plan(cap, &nr);
+                    if (B.verbose)
+                        std::fprintf(stderr,
+                                     "[cbm_build] seeds %7ld split above %3ld path cap %4ld: %3d rounds, %ld deltas, model %.1f us\n",
+                                     (long)seeds, (long)split, (long)cap, nr, (long)h->dptr[m], us);
+                    if (us < best_us) {
+                        best_us = us;
+                        best_len = cap;
+                        best_seeds = seeds;
+                        best_split = split;
+                    }
+                    if (forced_len > 0) break;
                 }
-                if (forced_len > 0) break;
             }
             if (forced_seeds >= 0 || m < 1024) break;
         }
         if (B.auto_depth && forced_len <= 0) {
             B.all_roots();
-            const double csr_us = B.csr_cost();
-            if (B.verbose)
-                std::fprintf(stderr, "[cbm_build] all rows in full: model %.1f us (best tree: %.1f us)\n", csr_us, best_us);
-            tree = best_us < csr_us;
+            for (int64_t split : split_choices) {
+                B.split_min = split;
+                const double csr_us = B.csr_cost();
+                if (B.verbose)
+                    std::fprintf(stderr, "[cbm_build] all rows in full, split above %ld: model %.1f us (best tree: %.1f us)\n",
+                                 (long)split, csr_us, best_us);
+                if (csr_us <= best_us) {
+                    best_us = csr_us;
+                    best_split = split;
+                    tree = false;
+                }
+            }
         }
         B.lap("tree + path model");
+    } else {
+        B.all_roots();
+        double best_us = 1e300;
+        for (int64_t split : split_choices) {
+            B.split_min = split;
+            const double us = B.csr_cost();
+            if (us < best_us) {
+                best_us = us;
+                best_split = split;
+            }
+        }
     }
+    B.split_min = best_split;
     if (tree)
         B.prim(best_seeds);
     else

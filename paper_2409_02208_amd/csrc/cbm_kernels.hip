@@ -50,6 +50,20 @@ template <int VEC>
 __device__ __forceinline__ void st(float* p, const Vec<VEC>& x) {
     *reinterpret_cast<Vec<VEC>*>(p) = x;
 }
+// Streaming store: rows of Y and partial sums are written once and not re-read by the same launch, so
+// they should not displace the gathered rows of X from L2.
+template <int VEC>
+__device__ __forceinline__ void st_stream(float* p, const Vec<VEC>& x) {
+    typedef float vec_t __attribute__((ext_vector_type(VEC)));
+    vec_t v;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) v[c] = x.v[c];
+    __builtin_nontemporal_store(v, reinterpret_cast<vec_t*>(p));
+}
+template <>
+__device__ __forceinline__ void st_stream<1>(float* p, const Vec<1>& x) {
+    __builtin_nontemporal_store(x.v[0], p);
+}
 
 // MODE 0: Y = A X.  MODE 1: Y = D^-1/2 (A v I) D^-1/2 X.  MODE 2: MODE 1 then max(., 0).
 // In MODE 1/2 a row that ANOTHER work item is compressed against (INTERNAL) is written
@@ -64,7 +78,7 @@ __device__ __forceinline__ void store_row(float* dst, Vec<VEC> acc, bool scale, 
             if (MODE == 2) acc.v[c] = fmaxf(acc.v[c], 0.0f);
         }
     }
-    st<VEC>(dst, acc);
+    st_stream<VEC>(dst, acc);
 }
 
 // One work item = one path of the compression tree (or one segment of a split row): start from
@@ -121,7 +135,7 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
     // lanes past the end of the stream hold entry 0 with weight 0: a delta that is never loaded
     auto load_e = [&](int chunk) -> uint32_t {
         const uint32_t idx = (uint32_t)chunk * LANES + sl;
-        return idx < len ? es[idx] : 0u;
+        return idx < len ? __builtin_nontemporal_load(es + idx) : 0u;  // read once: keep it out of the way of X
     };
     auto load_w = [&](uint32_t e, int chunk) -> float {  // +-d_col^-1/2 of a delta, d_row^-1/2 of a marker
         if (MODE == 0) return 0.0f;
@@ -186,7 +200,7 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
         if (b + 2 < nb) fetch(A, b + 2);
         if (b + 1 < nb) consume(B);
     }
-    if ((tk.len_flags & CBM_TASK_SEGMENT) && colok) st<VEC>(scratch + (int64_t)tk.row * ld_scratch + c0, acc);
+    if ((tk.len_flags & CBM_TASK_SEGMENT) && colok) st_stream<VEC>(scratch + (int64_t)tk.row * ld_scratch + c0, acc);
 }
 
 // Rows whose delta list was cut into segments: Y[x,:] = Y[r_x,:] + sum of the row's segment sums.
