@@ -1,0 +1,59 @@
+// Host builder + decompress on random matrices, built with ASan/UBSan by test_host_sanitizers.py; also checks that
+// every work item, entry and scratch slot the builder emits is in range (what the kernels rely on).
+#include <cstdio>
+#include <cstdlib>
+#include <random>
+#include <set>
+#include <vector>
+#include "cbm_internal.h"
+void cbm_set_error_detail(const char*, const char*) {}
+const char* cbm_get_error_detail() { return ""; }
+int main() {
+    std::mt19937 rng(1);
+    for (int trial = 0; trial < 60; ++trial) {
+        int m = 1 + rng() % 400, n = (trial % 3 == 0) ? m : 1 + rng() % 400;
+        double dens = (rng() % 100) / 300.0;
+        std::vector<int64_t> rp(m + 1, 0);
+        std::vector<int32_t> ci;
+        for (int i = 0; i < m; ++i) {
+            std::set<int> s;
+            int cnt = (int)(dens * n);
+            if (trial % 7 == 0 && i == 3) cnt = n;  // a long row -> segments
+            for (int c = 0; c < cnt; ++c) s.insert(rng() % n);
+            if (trial % 5 == 0 && i > 0 && i % 4 == 0) { s.clear(); for (int64_t p = rp[i-1]; p < rp[i]; ++p) s.insert(ci[p]); }  // duplicate rows
+            for (int c : s) ci.push_back(c);
+            rp[i + 1] = (int64_t)ci.size();
+        }
+        cbm_handle h;
+        h.opts = cbm_build_opts{};
+        h.opts.alpha = trial % 4;
+        h.opts.add_self_loops = (m == n) && (trial % 2);
+        h.opts.max_depth = (trial % 6 == 0) ? -1 : (trial % 6 == 1) ? 1 : (trial % 6 == 2) ? 0 : 16;
+        h.opts.seed_roots = (trial % 3) - 1;
+        h.opts.hub_cap = (trial % 4 == 0) ? 3 : 0;
+        h.opts.num_threads = 1 + trial % 4;
+        h.opts.flags = CBM_FLAG_HOST_ONLY;
+        cbm_status st = cbm_build_host(m, n, rp.data(), ci.data(), &h);
+        if (st != CBM_OK) { printf("build failed %d\n", st); return 1; }
+        std::vector<int64_t> orp(m + 1);
+        std::vector<int32_t> oci(h.stats.nnz + 1);
+        st = cbm_decompress_host(&h, orp.data(), oci.data());
+        if (st != CBM_OK) { printf("decompress failed %d\n", st); return 1; }
+        // bounds of the emitted stream / tasks
+        for (auto& t : h.tasks) {
+            uint32_t len = t.len_flags & CBM_TASK_LEN_MASK;
+            if ((size_t)t.start + len > h.stream.size()) { printf("task out of stream\n"); return 1; }
+            if (t.parent >= m) { printf("bad parent\n"); return 1; }
+            for (uint32_t i = 0; i < len; ++i) {
+                uint32_t e = h.stream[t.start + i];
+                uint32_t idx = e & CBM_ENTRY_INDEX_MASK;
+                if (e & CBM_ENTRY_MARK) { if ((int64_t)idx >= m) { printf("marker row out of range\n"); return 1; } }
+                else if ((int64_t)idx >= n) { printf("column out of range\n"); return 1; }
+            }
+            if ((t.len_flags & CBM_TASK_SEGMENT) && t.row >= h.num_slots) { printf("slot out of range\n"); return 1; }
+        }
+        for (auto& c : h.comb) if ((int64_t)c.start + (c.len_flags & CBM_TASK_LEN_MASK) > h.num_slots) { printf("comb slots\n"); return 1; }
+    }
+    printf("asan run ok\n");
+    return 0;
+}
