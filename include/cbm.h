@@ -56,7 +56,9 @@ typedef enum {
  *                longest work item, bandwidth) decides whether the tree pays
  *                for its extra dependent launches at all; on small graphs it
  *                does not, and every row is then stored in full (the paper's
- *                own finding for its small citation graphs, Section 3.3).  The
+ *                own finding for its small citation graphs, Section 3.3); the
+ *                same model drops a trailing round of dependent work when
+ *                storing its rows in full is cheaper than its launch.  The
  *                tree is cut into vertical paths, one work item each;
  *                dependent kernel launches per product = rounds of paths
  *                (cbm_stats), at most the depth.  Any value yields a valid CBM

@@ -149,6 +149,8 @@ struct Builder {
     bool is_split(int64_t x) const { return dlen(x) > split_min; }
     void tree_index();
     double plan(int64_t path_max, int32_t* nrounds_out);
+    double last_round_us = 0.0;
+    bool prune_last_round(int64_t path_max);
     double csr_cost() const;
     cbm_status emit(int32_t nrounds);
 };
@@ -476,12 +478,51 @@ double Builder::plan(int64_t path_max, int32_t* nrounds_out) {
     if (seg_entries > 0)
         us += kLaunchUs + std::max((double)split_len * kEntryUs, seg_entries * kRefRowBytes / (2.0 * kBytesPerUs));
     for (int r = 1; r <= nrounds; ++r) {
+        double round_us = 0.0;
         if (entries[r] + rows[r] > 0)
-            us += kLaunchUs + std::max(longest[r] * kEntryUs, (entries[r] + rows[r]) * kRefRowBytes / kBytesPerUs);
-        if (comb[r] > 0) us += kLaunchUs + comb[r] * kRefRowBytes / kBytesPerUs;
+            round_us += kLaunchUs + std::max(longest[r] * kEntryUs, (entries[r] + rows[r]) * kRefRowBytes / kBytesPerUs);
+        if (comb[r] > 0) round_us += kLaunchUs + comb[r] * kRefRowBytes / kBytesPerUs;
+        us += round_us;
+        last_round_us = round_us;
     }
     if (fixup && h->square_self_loops) us += kLaunchUs;
     return us;
+}
+
+// The paper prunes compression opportunities that do not pay for their overhead (Section 2.2, "Edge
+// Pruning").  Here the overhead that matters is a whole dependent launch: if storing the heads of the LAST
+// round in full costs less (a few more gathered rows in round 1) than that round's launch and latency, do
+// so; the round disappears.  Returns true if the tree changed.
+bool Builder::prune_last_round(int64_t path_max) {
+    int32_t nr = 0;
+    plan(path_max, &nr);
+    if (nr <= 1) return false;
+    int64_t extra = 0;
+    std::vector<int32_t> heads;
+    for (int64_t x = 0; x < m; ++x) {
+        if (round[x] != nr) continue;
+        const int32_t y = h->parent[x];
+        if (y >= 0 && next[y] == x) continue;  // continues a path of this round: moves with its head
+        heads.push_back((int32_t)x);
+        extra += rlen(x) - dlen(x);
+    }
+    if (last_round_us <= extra * kRefRowBytes / kBytesPerUs) return false;
+    if (verbose)
+        std::fprintf(stderr, "[cbm_build] round %d (%zu heads, model %.1f us) dropped: heads stored in full, +%ld deltas\n", nr,
+                     heads.size(), last_round_us, (long)extra);
+    std::vector<int64_t> len(m);
+    for (int64_t x = 0; x < m; ++x) len[x] = dlen(x);
+    for (int32_t x : heads) {
+        h->parent[x] = -1;
+        len[x] = rlen(x);
+    }
+    for (int64_t x = 0; x < m; ++x) h->dptr[x + 1] = h->dptr[x] + len[x];
+    for (int64_t i = 0; i < m; ++i) {  // the old level order is still parents-first
+        const int32_t x = order[i];
+        h->level[x] = h->parent[x] < 0 ? 1 : h->level[h->parent[x]] + 1;
+    }
+    tree_index();
+    return true;
 }
 
 // Modelled time of one product with every row stored in full (plain CSR on the same kernels).
@@ -727,10 +768,14 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
         }
     }
     B.split_min = best_split;
-    if (tree)
+    if (tree) {
         B.prim(best_seeds);
-    else
+        B.tree_index();
+        while (B.auto_depth && B.prune_last_round(best_len)) {  // part of the automatic policy only
+        }
+    } else {
         B.all_roots();
+    }
     std::vector<int64_t>().swap(B.optr);
     std::vector<int32_t>().swap(B.ochild);
     std::vector<int32_t>().swap(B.ow);
