@@ -292,6 +292,37 @@ def report(args, torch, cbm, wl, orc, csr_ref):
     print(json.dumps({"report": args.report, "rows": len(results)}), flush=True)
 
 
+def alpha_sweep(args, torch, cbm, wl):
+    """The paper's alpha experiment (Section 3.3, Fig. 1) on the synthetic graphs: runtime reduction against the
+    GPU CSR product and compression ratio, for alpha in {0,1,2,4,8,16,32,64}, with a tree forced (depth cap 16)."""
+    lines = ["# Edge-pruning threshold alpha on one MI355X (cf. Fig. 1 of the paper)", "",
+             "Normalised product, tree forced with `max_depth = 16` (the automatic policy is off so that alpha alone "
+             "decides what is compressed). runtime reduction = (T_CSR - T_CBM) / T_CSR against the same kernels on a handle "
+             "with every row stored in full; compression ratio = bytes(CSR) / bytes(CBM device arrays).", "",
+             "| graph | k | alpha | deltas/nnz | roots | depth / rounds | CBM ms | GPU CSR ms | runtime reduction | compression ratio |",
+             "|---|---|---|---|---|---|---|---|---|---|"]
+    for name in ("citation", "collaboration", "protein"):
+        k = DEFAULTS[name]["k"]
+        g = wl.make_graph(name)
+        X = torch.from_numpy(wl.gaussian_features(g.n, k, g.meta["seed"])).cuda()
+        Y = torch.empty((g.n, k), device="cuda")
+        hc = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=1)
+        ms_csr = time_steps(torch, lambda: cbm.cbm_spmm_normalized(hc, X, Y), args.steps, args.warmup)
+        cbm.cbm_free(hc)
+        for alpha in (0, 1, 2, 4, 8, 16, 32, 64):
+            h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha, max_depth=16)
+            st = cbm.cbm_stats(h)
+            ms = time_steps(torch, lambda: cbm.cbm_spmm_normalized(h, X, Y), args.steps, args.warmup)
+            nd = st["num_delta_plus"] + st["num_delta_minus"]
+            lines.append(f"| {name} | {k} | {alpha} | {nd / st['nnz']:.3f} | {st['num_roots']} | {st['depth']} / {st['rounds']} | "
+                         f"{ms:.4f} | {ms_csr:.4f} | {100 * (ms_csr - ms) / ms_csr:.0f} % | {st['bytes_csr'] / st['bytes_cbm']:.2f} |")
+            log(lines[-1])
+            cbm.cbm_free(h)
+    with open(args.alpha_sweep, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print(json.dumps({"alpha_sweep": args.alpha_sweep}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -306,6 +337,7 @@ def main():
     ap.add_argument("--no-gcn", action="store_true", help="skip the GCN inference timing")
     ap.add_argument("--no-csr", action="store_true", help="skip the all-roots (GPU CSR) comparison")
     ap.add_argument("--report", default="", help="walk all five graphs and write a markdown table to this file")
+    ap.add_argument("--alpha-sweep", default="", help="sweep the pruning threshold alpha on three graphs; write a table")
     ap.add_argument("--probe-gemm", action="store_true",
                     help="only time cbm_dense_matmul on the X.W shapes of the GCN configurations (for rocprofv3 counters)")
     ap.add_argument("--probe-copy", action="store_true",
@@ -344,6 +376,8 @@ def main():
             log(f"matmul {M}x{K} . {K}x{N}: {ms:.4f} ms, {res[-1]['tflops']:.1f} TFLOP/s")
         print(json.dumps({"probe": "gemm", "dtype": "f32", "peak_tflops": FP32_MFMA_PEAK_TFLOPS, "shapes": res}))
         return
+    if args.alpha_sweep:
+        return alpha_sweep(args, torch, cbm, wl)
     if args.report:
         return report(args, torch, cbm, wl, orc, csr_ref)
 
