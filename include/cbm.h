@@ -39,6 +39,12 @@ typedef enum {
 #define CBM_FLAG_HOST_ONLY 1u /* build the format but upload nothing to a GPU:
                                  cbm_stats / cbm_get_tree / cbm_decompress work,
                                  products return CBM_ERR_STATE                      */
+#define CBM_FLAG_EXACT_TREE 2u /* the chain of compression is a minimum-cost arborescence
+                                  of the pruned candidate digraph rooted at the virtual
+                                  vertex (Section 2.2, "Edge Pruning"), found exactly by
+                                  Edmonds' algorithm; max_depth and seed_roots are
+                                  ignored.  With hub_cap = max_candidates = -1 the
+                                  candidate digraph is the whole pruned distance graph. */
 
 /*
  * Build options.  A NULL pointer means all zeros, i.e. the defaults below.

@@ -140,6 +140,7 @@ struct Builder {
     std::vector<int32_t> ochild, ow;
     void find_candidates();
     void prim(int64_t seeds);
+    void arborescence();
     void all_roots();
     void delta_lists();
     // paths
@@ -344,6 +345,181 @@ void Builder::prim(int64_t seeds) {
     }
     h->dptr.assign(m + 1, 0);
     for (int64_t x = 0; x < m; ++x) h->dptr[x + 1] = h->dptr[x] + wsel[x];
+}
+
+// Exact minimum-cost arborescence of the candidate digraph rooted at the virtual vertex (Section 2.2,
+// "Edge Pruning": once edges are pruned by direction the chain of compression is an MCA).  Edmonds'
+// algorithm in Tarjan's form: every vertex keeps a meldable heap (leftist, with a lazy offset) of its
+// incoming edges; walking backwards along cheapest incoming edges either reaches finished ground or
+// closes a cycle, which is contracted (union-find, heaps melded, the chosen edge's cost taken off every
+// edge entering that vertex).  Contractions are undone in reverse order to read off the real edges.
+// Cost of an edge = (m + 1) * w + [non-virtual]: total weight first, then as few real edges as possible
+// (draws go to the virtual vertex).
+void Builder::arborescence() {
+    const int64_t V = m + 1, root = m;  // vertex m is the virtual null row
+    const int64_t E = m + (int64_t)ochild.size();
+    std::vector<int32_t> src(E), dst(E), lc(E, -1), rc(E, -1), rank(E, 1);
+    std::vector<int64_t> key(E), lazy(E, 0);
+    std::vector<int32_t> ew(E);  // Hamming weight of the edge (delta count)
+    for (int64_t x = 0; x < m; ++x) {  // virtual edges
+        src[x] = (int32_t)root;
+        dst[x] = (int32_t)x;
+        ew[x] = (int32_t)rlen(x);
+        key[x] = (int64_t)rlen(x) * V;
+    }
+    {
+        int64_t e = m;
+        for (int64_t y = 0; y < m; ++y)
+            for (int64_t p = optr[y]; p < optr[y + 1]; ++p, ++e) {
+                src[e] = (int32_t)y;
+                dst[e] = ochild[p];
+                ew[e] = ow[p];
+                key[e] = (int64_t)ow[p] * V + 1;
+            }
+    }
+    auto push_down = [&](int32_t a) {
+        if (lazy[a] == 0) return;
+        for (int32_t c : {lc[a], rc[a]})
+            if (c >= 0) {
+                key[c] += lazy[a];
+                lazy[c] += lazy[a];
+            }
+        lazy[a] = 0;
+    };
+    std::function<int32_t(int32_t, int32_t)> meld = [&](int32_t a, int32_t b) -> int32_t {
+        if (a < 0) return b;
+        if (b < 0) return a;
+        if (key[b] < key[a] || (key[b] == key[a] && b < a)) std::swap(a, b);
+        push_down(a);
+        rc[a] = meld(rc[a], b);
+        if (lc[a] < 0 || rank[lc[a]] < rank[rc[a]]) std::swap(lc[a], rc[a]);
+        rank[a] = rc[a] < 0 ? 1 : rank[rc[a]] + 1;
+        return a;
+    };
+    std::vector<int32_t> heap(V, -1);
+    for (int64_t e = 0; e < E; ++e) heap[dst[e]] = meld(heap[dst[e]], (int32_t)e);
+
+    // union-find with rollback (union by size, no path compression)
+    std::vector<int32_t> up(V), sz(V, 1);
+    for (int64_t v = 0; v < V; ++v) up[v] = (int32_t)v;
+    std::vector<std::pair<int32_t, int32_t>> log;  // (child root, parent root) of every union
+    auto find = [&](int32_t v) {
+        while (up[v] != v) v = up[v];
+        return v;
+    };
+    auto unite = [&](int32_t a, int32_t b) {  // a, b are roots; returns the new root
+        if (sz[a] < sz[b]) std::swap(a, b);
+        up[b] = a;
+        sz[a] += sz[b];
+        log.push_back({b, a});
+        return a;
+    };
+    struct Cycle {
+        size_t log_size;                                     // union-find state before the contraction
+        std::vector<std::pair<int32_t, int32_t>> members;    // (component at that time, its chosen in-edge)
+        int32_t merged;                                      // component after the contraction
+    };
+    std::vector<Cycle> cycles;
+    std::vector<int32_t> chosen(V, -1);  // chosen in-edge of a live component
+    std::vector<int32_t> state(V, 0);    // 0 = untouched, 1 = on the current walk, 2 = finished
+    state[root] = 2;
+    std::vector<int32_t> walk;
+    for (int64_t s = 0; s < m; ++s) {
+        int32_t u = find((int32_t)s);
+        if (state[u] != 0) continue;
+        walk.clear();
+        for (;;) {
+            if (state[u] == 2) break;  // reached finished ground
+            if (state[u] == 1) {
+                // u closes a cycle with the top of the walk: contract everything above u on the walk, and u
+                Cycle c;
+                c.log_size = log.size();
+                int32_t merged = u, h2 = -1;
+                for (;;) {
+                    const int32_t w = walk.back();
+                    walk.pop_back();
+                    c.members.push_back({w, chosen[w]});
+                    h2 = meld(h2, heap[w]);
+                    if (w == u) break;
+                }
+                for (auto& mw : c.members)
+                    if (mw.first != merged) merged = unite(find(merged), find(mw.first));
+                merged = find(merged);
+                heap[merged] = h2;
+                state[merged] = 0;
+                chosen[merged] = -1;
+                c.merged = merged;
+                cycles.push_back(std::move(c));
+                u = merged;
+                continue;
+            }
+            state[u] = 1;
+            walk.push_back(u);
+            // cheapest edge entering u from outside u
+            int32_t e = heap[u];
+            while (e >= 0 && find(src[e]) == u) {
+                push_down(e);
+                e = heap[u] = meld(lc[e], rc[e]);
+            }
+            // every vertex has its virtual edge, so a heap never runs dry before the root is reached
+            push_down(e);
+            heap[u] = meld(lc[e], rc[e]);
+            lc[e] = rc[e] = -1;
+            chosen[u] = e;
+            if (heap[u] >= 0) {  // reduced costs for the other edges entering u
+                key[heap[u]] -= key[e];
+                lazy[heap[u]] -= key[e];
+            }
+            u = find(src[e]);
+        }
+        for (int32_t w : walk) state[w] = 2;
+    }
+    // undo the contractions, newest first: inside a cycle every member keeps its chosen edge except the
+    // member that the cycle's own in-edge really enters
+    for (size_t i = cycles.size(); i-- > 0;) {
+        Cycle& c = cycles[i];
+        const int32_t e_in = chosen[c.merged];
+        while (log.size() > c.log_size) {
+            auto [child, parent] = log.back();
+            log.pop_back();
+            up[child] = child;
+            sz[parent] -= sz[child];
+        }
+        for (auto& mw : c.members) chosen[mw.first] = mw.second;
+        chosen[find(dst[e_in])] = e_in;
+    }
+    h->parent.assign(m, -1);
+    h->level.assign(m, 0);
+    h->dptr.assign(m + 1, 0);
+    for (int64_t x = 0; x < m; ++x) {
+        const int32_t e = chosen[x];
+        h->parent[x] = src[e] == root ? -1 : src[e];
+        h->dptr[x + 1] = h->dptr[x] + ew[e];
+    }
+    // levels by walking down from the rows stored in full
+    std::vector<int64_t> cp(m + 1, 0);
+    for (int64_t x = 0; x < m; ++x)
+        if (h->parent[x] >= 0) ++cp[h->parent[x] + 1];
+    for (int64_t x = 0; x < m; ++x) cp[x + 1] += cp[x];
+    std::vector<int32_t> ch(cp[m]);
+    {
+        std::vector<int64_t> fill(cp.begin(), cp.end() - 1);
+        for (int64_t x = 0; x < m; ++x)
+            if (h->parent[x] >= 0) ch[fill[h->parent[x]]++] = (int32_t)x;
+    }
+    std::vector<int32_t> frontier;
+    for (int64_t x = 0; x < m; ++x)
+        if (h->parent[x] < 0) {
+            h->level[x] = 1;
+            frontier.push_back((int32_t)x);
+        }
+    for (size_t i = 0; i < frontier.size(); ++i) {
+        const int32_t x = frontier[i];
+        for (int64_t q = cp[x]; q < cp[x + 1]; ++q) {
+            h->level[ch[q]] = h->level[x] + 1;
+            frontier.push_back(ch[q]);
+        }
+    }
 }
 
 // Delta lists (Eq. (2)) of every tree edge by list merge.
@@ -709,7 +885,22 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     std::vector<int64_t> split_choices = {kSplitMinDefault, kSplitLenDefault};
     if (std::getenv("CBM_SPLIT_MIN")) split_choices = {B.split_min};
     bool tree = B.max_depth != 1 && m > 1;
-    if (tree) {
+    const bool exact_tree = (o.flags & CBM_FLAG_EXACT_TREE) != 0;
+    if (tree && exact_tree) {
+        B.find_candidates();
+        B.arborescence();
+        B.tree_index();
+        double best_us = 1e300;
+        for (int64_t cap : kPathChoices) {
+            int32_t nr = 0;
+            const double us = B.plan(cap, &nr);
+            if (us < best_us) {
+                best_us = us;
+                best_len = cap;
+            }
+        }
+        B.lap("exact arborescence");
+    } else if (tree) {
         B.find_candidates();
         const int64_t forced_len = env_or("CBM_PATH_MAX", 0);
         const int64_t forced_seeds = o.seed_roots > 0 ? o.seed_roots : o.seed_roots < 0 ? 0 : env_or("CBM_SEED_ROOTS", -1);
@@ -768,7 +959,9 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
         }
     }
     B.split_min = best_split;
-    if (tree) {
+    if (tree && exact_tree) {
+        // keep the arborescence as found
+    } else if (tree) {
         B.prim(best_seeds);
         B.tree_index();
         while (B.auto_depth && B.prune_last_round(best_len)) {  // part of the automatic policy only

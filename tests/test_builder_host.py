@@ -98,6 +98,41 @@ def test_exact_mode_reaches_the_minimum_spanning_tree_weight(seed):
     assert s["num_delta_plus"] + s["num_delta_minus"] == sum(int(W[r[x], x]) for x in range(1, m + 1))
 
 
+@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("alpha", [0, 1, 2, 4])
+def test_exact_tree_is_a_minimum_cost_arborescence(seed, alpha):
+    # CBM_FLAG_EXACT_TREE on the complete candidate graph: same total weight as the oracle's Chu-Liu/Edmonds
+    rng = np.random.default_rng(900 + seed)
+    m, n = 45, 24
+    rows = _random_rows(rng, m, n, 0.4)
+    rows[7] = list(rows[6])
+    rows[20] = []
+    rowptr, colidx = _csr(rows)
+    h = cbm.cbm_build(m, n, rowptr, colidx, alpha=alpha, hub_cap=-1, max_candidates=-1, exact_tree=True, host_only=True)
+    s = _check_invariants(m, n, rowptr, colidx, h, alpha, False)
+    R = orc.adjacency_lists(m, rowptr, colidx)
+    W = orc.hamming_distance_graph(R)
+    r = orc.mca_rooted_at_virtual(W, orc.admissible_edges(W, max(alpha, 1)))  # draws go to the virtual edge: strict gain
+    want = sum(int(W[r[x], x]) for x in range(1, m + 1))
+    assert s["num_delta_plus"] + s["num_delta_minus"] == want
+
+
+def test_exact_tree_on_a_reduced_workload():
+    g = wl.collaboration_graph(n=6000)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=2, exact_tree=True, host_only=True)
+    s = cbm.cbm_stats(h)
+    hp = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=2, max_depth=-1, seed_roots=-1, host_only=True)
+    sp = cbm.cbm_stats(hp)
+    # same candidate edges: the arborescence can only be lighter than the Prim-grown tree
+    assert s["num_delta_plus"] + s["num_delta_minus"] <= sp["num_delta_plus"] + sp["num_delta_minus"]
+    rp, ci = cbm.cbm_decompress(h)
+    rp2, ci2 = cbm.cbm_decompress(hp)
+    assert np.array_equal(rp, rp2) and np.array_equal(ci, ci2)
+    t = cbm.cbm_get_tree(h)
+    comp = t["parent"] >= 0
+    assert np.all(t["level"][comp] == t["level"][t["parent"][comp]] + 1) and np.all(t["level"] >= 1)
+
+
 def test_depth_cap_and_pruning_options():
     g = wl.tiny_graph()
     full = cbm.cbm_stats(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=-1, seed_roots=-1, host_only=True))
