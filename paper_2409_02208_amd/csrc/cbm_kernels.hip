@@ -219,10 +219,22 @@ __global__ __launch_bounds__(256) void cbm_combine_kernel(const CbmTask* __restr
 #pragma unroll
     for (int c = 0; c < VEC; ++c) acc.v[c] = 0.0f;
     if (tk.parent >= 0) acc = ld<VEC>(Y + (int64_t)tk.parent * ldy + c0);
-    for (uint32_t s = 0; s < nseg; ++s) {
-        const Vec<VEC> p = ld<VEC>(scratch + (int64_t)(tk.start + s) * ld_scratch + c0);
+    const float* part = scratch + (int64_t)tk.start * ld_scratch + c0;
+    for (uint32_t s0 = 0; s0 < nseg; s0 += 8) {  // eight independent loads in flight, added in segment order
+        Vec<VEC> p[8];
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) acc.v[c] += p.v[c];
+        for (int u = 0; u < 8; ++u) {
+            if (s0 + u < nseg) {
+                p[u] = ld<VEC>(part + (int64_t)(s0 + u) * ld_scratch);
+            } else {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) p[u].v[c] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) acc.v[c] += p[u].v[c];
     }
     store_row<VEC, MODE>(Y + (int64_t)tk.row * ldy + c0, acc, !(tk.len_flags & CBM_TASK_INTERNAL),
                          MODE != 0 ? dinv[tk.row] : 1.0f);

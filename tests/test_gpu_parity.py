@@ -299,3 +299,40 @@ def test_profile_records(env, graphs):
     assert len(levels) == s["rounds"] <= s["depth"]
     assert sum(r["deltas"] for r in levels) == s["num_delta_plus"] + s["num_delta_minus"]
     assert all(r["milliseconds"] > 0 for r in recs)
+
+
+def test_products_can_be_captured_in_a_hip_graph(env, graphs):
+    # the product calls only enqueue kernels (after the first call has sized the scratch), so a caller may
+    # capture them; every replay is checked against the eager result, with eager work between replays
+    torch, cbm = env
+    g = graphs["collaboration"]
+    k, hidden, f_out = 32, 16, 4
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=16)
+    W0 = torch.from_numpy(wl.glorot_uniform(k, hidden, 1)).cuda()
+    W1 = torch.from_numpy(wl.glorot_uniform(hidden, f_out, 2)).cuda()
+    ws = torch.empty(cbm.cbm_gcn2_workspace_bytes(h, k, hidden, f_out), dtype=torch.uint8, device="cuda")
+    X = torch.from_numpy(wl.gaussian_features(g.n, k, 1)).cuda()
+    Y = torch.empty((g.n, k), device="cuda")
+    out = torch.empty((g.n, f_out), device="cuda")
+    cbm.cbm_spmm_normalized(h, X, Y)          # first calls outside the capture: scratch is sized here
+    cbm.cbm_gcn2_forward(h, X, W0, W1, out, ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cbm.cbm_spmm_normalized(h, X, Y)
+        cbm.cbm_gcn2_forward(h, X, W0, W1, out, ws)
+    for it in range(4):
+        X.copy_(torch.from_numpy(wl.gaussian_features(g.n, k, 10 + it)).cuda())
+        Y.fill_(float("nan"))
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got_y, got_out = Y.clone(), out.clone()
+        Y2 = torch.empty_like(Y)
+        out2 = torch.empty_like(out)
+        cbm.cbm_spmm_normalized(h, X, Y2)     # eager, between replays
+        cbm.cbm_gcn2_forward(h, X, W0, W1, out2, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(got_y, Y2) and torch.equal(got_out, out2)
+    ref = orc.spmm_csr_normalized(g.rowptr, g.colidx, X.cpu().numpy())
+    assert row_scaled_error(got_y.cpu().numpy(), ref) <= TOL
