@@ -134,8 +134,10 @@ cbm_status cbm_build(int64_t m, int64_t n, const int64_t* rowptr, const int32_t*
  * cbm_spmm -- Y = A . X  (Eq. (5), Algorithm 1).
  *   X   device, n x k row-major fp32, leading dimension ldx >= k (in floats).
  *   Y   device, m x k row-major fp32, leading dimension ldy >= k.  Fully
- *       overwritten (it need not be zeroed) and must not overlap X.  The tree
- *       update runs in place in Y (Property 3).
+ *       overwritten (it need not be zeroed).  The byte ranges spanned by X and
+ *       Y must be disjoint (CBM_ERR_INVALID_ARG otherwise, also for column
+ *       slices interleaved in one buffer).  The tree update runs in place in Y
+ *       (Property 3).
  *   hip_stream  a hipStream_t (NULL = default stream).  The call only enqueues
  *       kernels and returns; the caller synchronises.
  * If the handle was built with add_self_loops the product is (A v I) . X.

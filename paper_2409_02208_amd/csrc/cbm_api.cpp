@@ -22,6 +22,11 @@ cbm_status check_product_args(const cbm_handle* h, const float* X, int64_t ldx, 
     if (!h || k <= 0 || ldx < k || ldy < k) return CBM_ERR_INVALID_ARG;
     if ((!X && h->n > 0) || (!Y && h->m > 0)) return CBM_ERR_INVALID_ARG;  // an empty operand may be NULL
     if (!h->on_device) return CBM_ERR_STATE;
+    if (X && Y && h->m > 0 && h->n > 0) {  // Y is written while X is still being gathered: they must not overlap
+        const uintptr_t xb = (uintptr_t)X, xe = xb + ((uintptr_t)(h->n - 1) * ldx + k) * sizeof(float);
+        const uintptr_t yb = (uintptr_t)Y, ye = yb + ((uintptr_t)(h->m - 1) * ldy + k) * sizeof(float);
+        if (xb < ye && yb < xe) return CBM_ERR_INVALID_ARG;
+    }
     return CBM_OK;
 }
 

@@ -227,6 +227,13 @@ def test_argument_errors_on_device_handle(env, graphs):
     with pytest.raises(cbm.CbmError) as e:
         cbm.cbm_spmm_normalized(h, X, Y)
     assert e.value.status == 6
+    with pytest.raises(cbm.CbmError) as e:  # the output may not overlap the input
+        cbm.cbm_spmm(h, X, X)
+    assert e.value.status == 1
+    W = torch.zeros((g.n, 16), device="cuda")
+    with pytest.raises(cbm.CbmError) as e:  # not even as interleaved column slices of one buffer
+        cbm.cbm_spmm(h, W[:, :8], W[:, 8:])
+    assert e.value.status == 1
 
 
 @pytest.mark.parametrize("M,N,K", [(1000, 64, 500), (777, 3, 64), (513, 112, 256), (256, 256, 256), (130, 33, 7),
