@@ -238,6 +238,8 @@ def report(args, torch, cbm, wl, orc, csr_ref):
              "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
     gcn_lines = ["", "| graph | GCN shape | CBM ms | as HIP graph replay ms | with CSR handle ms | speedup | "
                  "X.W0 ms (TFLOP/s, frac of fp32 MFMA peak) | H.W1 ms | parity err |", "|---|---|---|---|---|---|---|---|---|"]
+    agg_lines = ["", "Other aggregators on the same handles (M = A v I), k as above: ms per product, CBM handle / CSR handle.", "",
+                 "| graph | k | normalised | mean (D^-1 M X) | GIN (M X + 1.25 X) | plain (M X) |", "|---|---|---|---|---|---|"]
     results = []
     for name, ks in plan:
         d = DEFAULTS[name]
@@ -261,6 +263,17 @@ def report(args, torch, cbm, wl, orc, csr_ref):
                          f"{ob['value']:.2f} | {r['parity_err']:.1e} |")
             results.append(dict(workload=name, k=k, **{kk: vv for kk, vv in r.items() if kk != "stats"}, stats=st,
                                 cpu_csr_omp=cpu, cpu_oracle=ob))
+        if name in ("collaboration", "protein", "rmat"):
+            k = ks[-1]
+            X = torch.from_numpy(wl.gaussian_features(g.n, k, g.meta["seed"])).cuda()
+            Y = torch.empty_like(X)
+            row = {}
+            for label, fn in (("normalised", cbm.cbm_spmm_normalized), ("mean", cbm.cbm_spmm_mean),
+                              ("gin", lambda hh, x, y: cbm.cbm_spmm_gin(hh, 0.25, x, y)), ("plain", cbm.cbm_spmm)):
+                row[label] = [time_steps(torch, lambda hh=hh, fn=fn: fn(hh, X, Y), args.steps, args.warmup) for hh in (h, hc)]
+            agg_lines.append(f"| {name} | {k} | " + " | ".join(f"{a:.4f} / {b:.4f}" for a, b in row.values()) + " |")
+            results.append(dict(workload=name, k=k, aggregators_ms_cbm_csr=row))
+            del X, Y
         if d["gcn"]:
             gc = bench_gcn(torch, cbm, wl, orc, g, h, hc, d["gcn"], args.steps, args.warmup)
             e = gc["max_row_scaled_error_vs_oracle"]
@@ -288,7 +301,7 @@ def report(args, torch, cbm, wl, orc, csr_ref):
             cbm.cbm_free(hp)
         cbm.cbm_free(h)
         cbm.cbm_free(hc)
-    text = "\n".join(lines + gcn_lines) + "\n\nPaper context (not comparable): ~5x SpMM and up to 3x GCN inference over " \
+    text = "\n".join(lines + gcn_lines + agg_lines) + "\n\nPaper context (not comparable): ~5x SpMM and up to 3x GCN inference over " \
         "MKL CSR on a 16-core Xeon Gold 6130, relative figures on real datasets.\n"
     os.makedirs(os.path.dirname(os.path.abspath(args.report)), exist_ok=True)
     with open(args.report, "w") as f:

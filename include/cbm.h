@@ -165,6 +165,20 @@ cbm_status cbm_spmm_normalized_relu(const cbm_handle* h, const float* X, int64_t
                                     int64_t ldy, void* hip_stream);
 
 /*
+ * Two more aggregators of the GNN layers the paper names as targets (Section 1: GraphSAGE, GIN), as
+ * epilogues of the same kernels; M is the compressed matrix (A, or A v I if built with add_self_loops).
+ *   cbm_spmm_mean  Y = D^-1 M X, D = row sums of M: the mean of each row's entries (GraphSAGE's mean
+ *                  aggregator); a row of M with no entry gives a zero row.
+ *   cbm_spmm_gin   Y = M X + (1 + eps) X (GIN's aggregator); needs m == n.
+ * Arguments as for cbm_spmm.  For a symmetric M the backward pass of all products here is the
+ * same product applied to the output gradient (M^T = M).
+ */
+cbm_status cbm_spmm_mean(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
+                         void* hip_stream);
+cbm_status cbm_spmm_gin(const cbm_handle* h, float eps, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
+                        void* hip_stream);
+
+/*
  * cbm_dense_matmul -- C = A . B for dense row-major fp32 device matrices
  * (the X . W products of Eq. (1)); fp32 MFMA, fp32 accumulation.
  *   A  M x K (lda >= K),  B  K x N (ldb >= N),  C  M x N (ldc >= N), no overlap.

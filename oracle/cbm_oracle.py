@@ -12,7 +12,8 @@ compressed against (r_x = 0 means "stored in full").
 
 Parity pins (see tests/test_oracle_*.py): a hand-worked example, dense brute
 force, closed forms (complete graph, cycle, lower-triangular/cumsum, the
-eigen-identity of the normalised adjacency), library MST / arborescence weights,
+eigen-identity of the normalised adjacency, neighbour mean / GIN sum on the
+complete graph and the cycle), library MST / arborescence weights,
 and exhaustive enumeration of all arborescences on tiny inputs.  Every function
 below is covered by at least one of them; none is "parity unpinned".
 """
@@ -94,6 +95,32 @@ def spmm_csr_normalized(rowptr, colidx, X: np.ndarray, rows=None, d=None) -> np.
         if not np.any(cols == i):
             cols = np.concatenate((cols, [i]))
         Y[o] = s[i] * (s[cols, None] * X[cols].astype(np.float64)).sum(axis=0)
+    return Y
+
+
+def spmm_csr_mean(rowptr, colidx, X: np.ndarray, rows=None) -> np.ndarray:
+    """Y[i,:] = mean_{j in a_i} X[j,:], a zero row where a_i is empty: the mean
+    aggregator of the GraphSAGE layer (one of the layers Section 1 names as built
+    on the same product)."""
+    rows = range(len(rowptr) - 1) if rows is None else rows
+    Y = np.zeros((len(rows), X.shape[1]), dtype=np.float64)
+    for o, i in enumerate(rows):
+        cols = colidx[int(rowptr[i]):int(rowptr[i + 1])]
+        if len(cols):
+            Y[o] = X[cols].sum(axis=0, dtype=np.float64) / len(cols)
+    return Y
+
+
+def spmm_csr_gin(rowptr, colidx, X: np.ndarray, eps: float, rows=None) -> np.ndarray:
+    """Y[i,:] = (1 + eps) X[i,:] + sum_{j in a_i} X[j,:]: the aggregator of the GIN
+    layer (Section 1 names it among the layers built on the same product)."""
+    rows = range(len(rowptr) - 1) if rows is None else rows
+    Y = np.zeros((len(rows), X.shape[1]), dtype=np.float64)
+    for o, i in enumerate(rows):
+        cols = colidx[int(rowptr[i]):int(rowptr[i + 1])]
+        Y[o] = (1.0 + float(eps)) * X[i].astype(np.float64)
+        if len(cols):
+            Y[o] += X[cols].sum(axis=0, dtype=np.float64)
     return Y
 
 

@@ -16,7 +16,8 @@ CBM_FLAG_HOST_ONLY = 1
 CBM_FLAG_EXACT_TREE = 2
 
 EXPORTS = [
-    "cbm_build", "cbm_spmm", "cbm_spmm_normalized", "cbm_spmm_normalized_relu", "cbm_dense_matmul",
+    "cbm_build", "cbm_spmm", "cbm_spmm_normalized", "cbm_spmm_normalized_relu", "cbm_spmm_mean", "cbm_spmm_gin",
+    "cbm_dense_matmul",
     "cbm_gcn2_forward", "cbm_gcn2_workspace_bytes", "cbm_stats", "cbm_get_tree", "cbm_decompress",
     "cbm_profile_enable", "cbm_profile_read", "cbm_free", "cbm_status_string", "cbm_last_error_detail",
 ]
@@ -68,8 +69,9 @@ def _lib():
         lib = C.CDLL(LIB_PATH)
         vp, i64, i32, f32p = C.c_void_p, C.c_int64, C.c_int32, C.c_void_p
         lib.cbm_build.argtypes = [i64, i64, vp, vp, C.POINTER(cbm_build_opts), C.POINTER(vp)]
-        for name in ("cbm_spmm", "cbm_spmm_normalized", "cbm_spmm_normalized_relu"):
+        for name in ("cbm_spmm", "cbm_spmm_normalized", "cbm_spmm_normalized_relu", "cbm_spmm_mean"):
             getattr(lib, name).argtypes = [vp, f32p, i64, i32, f32p, i64, vp]
+        lib.cbm_spmm_gin.argtypes = [vp, C.c_float, f32p, i64, i32, f32p, i64, vp]
         lib.cbm_dense_matmul.argtypes = [i64, i32, i32, f32p, i64, f32p, i64, f32p, i64, vp]
         lib.cbm_gcn2_forward.argtypes = [vp, f32p, i32, f32p, i32, f32p, i32, f32p, vp, C.c_size_t, vp]
         lib.cbm_gcn2_workspace_bytes.argtypes = [vp, i32, i32, i32]
@@ -162,6 +164,19 @@ def cbm_spmm_normalized(h: Handle, X, Y, stream=None):
 
 def cbm_spmm_normalized_relu(h: Handle, X, Y, stream=None):
     return _product("cbm_spmm_normalized_relu", h, X, Y, stream)
+
+
+def cbm_spmm_mean(h: Handle, X, Y, stream=None):
+    return _product("cbm_spmm_mean", h, X, Y, stream)
+
+
+def cbm_spmm_gin(h: Handle, eps: float, X, Y, stream=None):
+    xp, ldx = _dev_f32(X, "X")
+    yp, ldy = _dev_f32(Y, "Y")
+    if X.shape[1] != Y.shape[1]:
+        raise ValueError("X and Y must have the same number of columns")
+    _check(_lib().cbm_spmm_gin(h.ptr, float(eps), xp, ldx, X.shape[1], yp, ldy, _stream_ptr(stream)), "cbm_spmm_gin")
+    return Y
 
 
 def cbm_dense_matmul(A, B, Cout, stream=None):

@@ -62,7 +62,7 @@ cbm_status cbm_spmm(const cbm_handle* h, const float* X, int64_t ldx, int32_t k,
                     void* hip_stream) {
     cbm_status st = check_product_args(h, X, ldx, k, Y, ldy);
     if (st != CBM_OK) return st;
-    return cbm_launch_product(h, X, ldx, k, Y, ldy, CBM_EPI_NONE, hip_stream);
+    return cbm_launch_product(h, X, ldx, k, Y, ldy, CBM_EPI_NONE, 0.0f, hip_stream);
 }
 
 cbm_status cbm_spmm_normalized(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
@@ -70,7 +70,7 @@ cbm_status cbm_spmm_normalized(const cbm_handle* h, const float* X, int64_t ldx,
     cbm_status st = check_product_args(h, X, ldx, k, Y, ldy);
     if (st != CBM_OK) return st;
     if (!h->square_self_loops) return CBM_ERR_STATE;
-    return cbm_launch_product(h, X, ldx, k, Y, ldy, CBM_EPI_ROWSCALE, hip_stream);
+    return cbm_launch_product(h, X, ldx, k, Y, ldy, CBM_EPI_ROWSCALE, 0.0f, hip_stream);
 }
 
 cbm_status cbm_spmm_normalized_relu(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y,
@@ -78,7 +78,22 @@ cbm_status cbm_spmm_normalized_relu(const cbm_handle* h, const float* X, int64_t
     cbm_status st = check_product_args(h, X, ldx, k, Y, ldy);
     if (st != CBM_OK) return st;
     if (!h->square_self_loops) return CBM_ERR_STATE;
-    return cbm_launch_product(h, X, ldx, k, Y, ldy, CBM_EPI_ROWSCALE_RELU, hip_stream);
+    return cbm_launch_product(h, X, ldx, k, Y, ldy, CBM_EPI_ROWSCALE_RELU, 0.0f, hip_stream);
+}
+
+cbm_status cbm_spmm_mean(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
+                         void* hip_stream) {
+    cbm_status st = check_product_args(h, X, ldx, k, Y, ldy);
+    if (st != CBM_OK) return st;
+    return cbm_launch_product(h, X, ldx, k, Y, ldy, CBM_EPI_MEAN, 0.0f, hip_stream);
+}
+
+cbm_status cbm_spmm_gin(const cbm_handle* h, float eps, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
+                        void* hip_stream) {
+    cbm_status st = check_product_args(h, X, ldx, k, Y, ldy);
+    if (st != CBM_OK) return st;
+    if (h->m != h->n) return CBM_ERR_STATE;
+    return cbm_launch_product(h, X, ldx, k, Y, ldy, CBM_EPI_SELF, 1.0f + eps, hip_stream);
 }
 
 cbm_status cbm_dense_matmul(int64_t M, int32_t N, int32_t K, const float* A, int64_t lda, const float* B, int64_t ldb,
@@ -112,10 +127,10 @@ cbm_status cbm_gcn2_forward(const cbm_handle* h, const float* X, int32_t f_in, c
     float* Z1 = (float*)(ws + 2 * r((size_t)n * hidden * 4));
     cbm_status st;
     if ((st = cbm_launch_gemm(n, hidden, f_in, X, f_in, W0, hidden, Z0, hidden, hip_stream)) != CBM_OK) return st;
-    if ((st = cbm_launch_product(h, Z0, hidden, hidden, H, hidden, CBM_EPI_ROWSCALE_RELU, hip_stream)) != CBM_OK)
+    if ((st = cbm_launch_product(h, Z0, hidden, hidden, H, hidden, CBM_EPI_ROWSCALE_RELU, 0.0f, hip_stream)) != CBM_OK)
         return st;
     if ((st = cbm_launch_gemm(n, f_out, hidden, H, hidden, W1, f_out, Z1, f_out, hip_stream)) != CBM_OK) return st;
-    return cbm_launch_product(h, Z1, f_out, f_out, out, f_out, CBM_EPI_ROWSCALE, hip_stream);
+    return cbm_launch_product(h, Z1, f_out, f_out, out, f_out, CBM_EPI_ROWSCALE, 0.0f, hip_stream);
 }
 
 cbm_status cbm_stats(const cbm_handle* h, cbm_stats_t* out) {

@@ -864,6 +864,8 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     for (int64_t i = 0; i < m; ++i) h->rownnz[i] = (int32_t)(B.rowptr[i + 1] - B.rowptr[i]);
     B.lap("validate + A v I");
 
+    h->rinv.resize(m);  // 1/nnz per row: the mean aggregator's row weight
+    for (int64_t i = 0; i < m; ++i) h->rinv[i] = B.rlen(i) > 0 ? (float)(1.0 / (double)B.rlen(i)) : 0.0f;
     if (h->square_self_loops) {  // D^-1/2 of A v I
         h->dinv.resize(m);
         for (int64_t i = 0; i < m; ++i) h->dinv[i] = (float)(1.0 / std::sqrt((double)B.rlen(i)));

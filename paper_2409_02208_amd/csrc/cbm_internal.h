@@ -32,7 +32,7 @@ constexpr int CBM_XCD = 8;  // accelerator complex dies of an MI355X; workgroup 
 
 struct CbmLevel {
     // one ROUND of dependent work (the struct keeps its first name: a round of single-row paths is a tree level)
-    int64_t task_begin = 0, task_count = 0;        // into tasks[]: paths headed in this round (+ all segments, round 1)
+    int64_t task_begin = 0, task_count = 0;        // into tasks[]: paths headed in this round
     int64_t comb_begin = 0, comb_count = 0;        // into comb[]: split rows of this round
     int64_t deltas = 0;                            // delta entries gathered by the round's main launch
     int64_t parent_reads = 0;                      // tasks in the main launch with a parent
@@ -56,6 +56,7 @@ struct cbm_handle {
     std::vector<uint32_t> dcol;    // Delta+ then Delta- of each row, sign in bit 31 (host copy, by row)
     std::vector<uint32_t> stream;  // the same deltas in work-item order, with row markers (uploaded)
     std::vector<float> dinv;       // d_x^-1/2 (square_self_loops only)
+    std::vector<float> rinv;       // 1 / nnz of each compressed row, 0 for an empty row
     std::vector<CbmTask> tasks;
     std::vector<CbmTask> comb;     // split rows: start = first scratch slot, len = number of segments
     std::vector<int32_t> internal_rows;
@@ -72,6 +73,7 @@ struct cbm_handle {
     CbmTask* d_comb = nullptr;
     uint32_t* d_stream = nullptr;
     float* d_dinv = nullptr;
+    float* d_rinv = nullptr;
     int32_t* d_internal = nullptr;
     mutable float* d_scratch = nullptr;  // num_slots x scratch_k floats, sized on first use
     mutable int64_t scratch_k = 0;
@@ -91,11 +93,11 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* rowptr, const int
 cbm_status cbm_decompress_host(const cbm_handle* h, int64_t* rowptr, int32_t* colidx);
 
 // device side (cbm_kernels.hip)
-enum CbmEpilogue { CBM_EPI_NONE = 0, CBM_EPI_ROWSCALE = 1, CBM_EPI_ROWSCALE_RELU = 2 };
+enum CbmEpilogue { CBM_EPI_NONE = 0, CBM_EPI_ROWSCALE = 1, CBM_EPI_ROWSCALE_RELU = 2, CBM_EPI_MEAN = 3, CBM_EPI_SELF = 4 };
 cbm_status cbm_upload(cbm_handle* h);
 void cbm_release_device(cbm_handle* h);
 cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
-                              CbmEpilogue epi, void* stream);
+                              CbmEpilogue epi, float self_weight, void* stream);
 // dense fp32 MFMA matmul (cbm_gemm.hip)
 cbm_status cbm_launch_gemm(int64_t M, int32_t N, int32_t K, const float* A, int64_t lda, const float* B, int64_t ldb,
                            float* C, int64_t ldc, void* stream);

@@ -65,17 +65,33 @@ __device__ __forceinline__ void st_stream<1>(float* p, const Vec<1>& x) {
     __builtin_nontemporal_store(x.v[0], p);
 }
 
-// MODE 0: Y = A X.  MODE 1: Y = D^-1/2 (A v I) D^-1/2 X.  MODE 2: MODE 1 then max(., 0).
-// In MODE 1/2 a row that ANOTHER work item is compressed against (INTERNAL) is written
-// unscaled, because that work item adds its unscaled sum (the row scale belongs to the update
-// step, Section 2.2); cbm_rowscale_kernel scales those rows once every round is done.
+// MODE 0: Y = M X (M = the compressed matrix).
+// MODE 1: Y = D^-1/2 M D^-1/2 X with M = A v I (the normalised adjacency).  MODE 2: MODE 1 then max(., 0).
+// MODE 3: Y = D^-1 M X (mean over each row's entries: the GraphSAGE mean aggregator).
+// MODE 4: Y = M X + s X (s = 1 + eps: the GIN aggregator).
+// Column weights multiply gathered rows, row weights the stored row; the self term of MODE 4 is the
+// row's own X row, fetched by its marker entry like any gathered row.
+// A row that ANOTHER work item is compressed against (INTERNAL) is written as the bare running sum,
+// because that work item continues from it (the row scale belongs to the update step, Section 2.2);
+// cbm_finish_kernel applies the row weight / self term to those rows once every round is done.
+template <int MODE>
+struct Mode {
+    static constexpr bool wcol = MODE == 1 || MODE == 2;
+    static constexpr bool wrow = MODE == 1 || MODE == 2 || MODE == 3;
+    static constexpr bool relu = MODE == 2;
+    static constexpr bool self = MODE == 4;
+    static constexpr bool weights = wcol || wrow;
+};
+
+// out = finish(acc): acc (+ self_w * own X row) (* row weight) (then ReLU)
 template <int VEC, int MODE>
-__device__ __forceinline__ void store_row(float* dst, Vec<VEC> acc, bool scale, float s) {
-    if (MODE != 0 && scale) {
+__device__ __forceinline__ void store_row(float* dst, Vec<VEC> acc, bool finish, float w, const Vec<VEC>& own, float self_w) {
+    if (finish) {
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
-            acc.v[c] *= s;
-            if (MODE == 2) acc.v[c] = fmaxf(acc.v[c], 0.0f);
+            if (Mode<MODE>::self) acc.v[c] = fmaf(self_w, own.v[c], acc.v[c]);
+            if (Mode<MODE>::wrow) acc.v[c] *= w;
+            if (Mode<MODE>::relu) acc.v[c] = fmaxf(acc.v[c], 0.0f);
         }
     }
     st_stream<VEC>(dst, acc);
@@ -104,7 +120,9 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
                                                         const uint32_t* __restrict__ stream,
                                                         const float* __restrict__ X, int64_t ldx, float* Y,
                                                         int64_t ldy, float* scratch, int64_t ld_scratch,
-                                                        const float* __restrict__ dinv, int k) {
+                                                        const float* __restrict__ cw, const float* __restrict__ rw,
+                                                        float self_w, int k) {
+    using M = Mode<MODE>;
     constexpr int G = 64 / LANES;                  // work items per wave
     constexpr int U = LANES < UMAX ? LANES : UMAX;  // X rows per batch
     constexpr int BPC = LANES / U;                  // batches per chunk of entries
@@ -137,11 +155,13 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
         const uint32_t idx = (uint32_t)chunk * LANES + sl;
         return idx < len ? __builtin_nontemporal_load(es + idx) : 0u;  // read once: keep it out of the way of X
     };
-    auto load_w = [&](uint32_t e, int chunk) -> float {  // +-d_col^-1/2 of a delta, d_row^-1/2 of a marker
-        if (MODE == 0) return 0.0f;
+    auto load_w = [&](uint32_t e, int chunk) -> float {  // signed column weight of a delta, row weight of a marker
+        if (!M::weights) return 0.0f;
         const uint32_t idx = (uint32_t)chunk * LANES + sl;
         if (idx >= len) return 0.0f;
-        const float w = dinv[e & CBM_ENTRY_INDEX_MASK];
+        if (e & CBM_ENTRY_MARK) return M::wrow ? rw[e & CBM_ENTRY_INDEX_MASK] : 0.0f;
+        if (!M::wcol) return 0.0f;
+        const float w = cw[e & CBM_ENTRY_INDEX_MASK];
         return (e & CBM_DELTA_MINUS) ? -w : w;
     };
     uint32_t e0 = load_e(0), e1 = load_e(1), e2 = load_e(2);
@@ -166,8 +186,11 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             S.e[u] = (uint32_t)__shfl((int)e0, off + u, LANES);
-            S.w[u] = MODE != 0 ? __shfl(w0, off + u, LANES) : 0.0f;
-            if ((uint32_t)(b * U + u) < len && !(S.e[u] & CBM_ENTRY_MARK) && colok) {
+            S.w[u] = M::weights ? __shfl(w0, off + u, LANES) : 0.0f;
+            // a delta gathers its column's row of X; in MODE 4 a marker gathers the row's own X row
+            const bool gather = !(S.e[u] & CBM_ENTRY_MARK) ||
+                                (M::self && !(S.e[u] & CBM_ENTRY_INTERNAL));
+            if ((uint32_t)(b * U + u) < len && gather && colok) {
                 S.x[u] = ld<VEC>(X + (int64_t)(S.e[u] & CBM_ENTRY_INDEX_MASK) * ldx + c0);
             } else {
 #pragma unroll
@@ -181,8 +204,8 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
             if (S.e[u] & CBM_ENTRY_MARK) {
                 if (colok)
                     store_row<VEC, MODE>(Y + (int64_t)(S.e[u] & CBM_ENTRY_INDEX_MASK) * ldy + c0, acc,
-                                         !(S.e[u] & CBM_ENTRY_INTERNAL), S.w[u]);
-            } else if (MODE != 0) {
+                                         !(S.e[u] & CBM_ENTRY_INTERNAL), S.w[u], S.x[u], self_w);
+            } else if (M::wcol) {
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(S.w[u], S.x[u].v[c], acc.v[c]);
             } else {
@@ -205,9 +228,10 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
 
 // Rows whose delta list was cut into segments: Y[x,:] = Y[r_x,:] + sum of the row's segment sums.
 template <int VEC, int LANES, int MODE>
-__global__ __launch_bounds__(256) void cbm_combine_kernel(const CbmTask* __restrict__ comb, int64_t ncomb, float* Y,
+__global__ __launch_bounds__(256) void cbm_combine_kernel(const CbmTask* __restrict__ comb, int64_t ncomb,
+                                                          const float* __restrict__ X, int64_t ldx, float* Y,
                                                           int64_t ldy, const float* scratch, int64_t ld_scratch,
-                                                          const float* __restrict__ dinv, int k) {
+                                                          const float* __restrict__ rw, float self_w, int k) {
     constexpr int G = 64 / LANES;
     const int lane = threadIdx.x & 63;
     const int64_t t = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * G + lane / LANES;
@@ -236,22 +260,29 @@ __global__ __launch_bounds__(256) void cbm_combine_kernel(const CbmTask* __restr
 #pragma unroll
             for (int c = 0; c < VEC; ++c) acc.v[c] += p[u].v[c];
     }
-    store_row<VEC, MODE>(Y + (int64_t)tk.row * ldy + c0, acc, !(tk.len_flags & CBM_TASK_INTERNAL),
-                         MODE != 0 ? dinv[tk.row] : 1.0f);
+    const bool finish = !(tk.len_flags & CBM_TASK_INTERNAL);
+    Vec<VEC> own;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) own.v[c] = 0.0f;
+    if (Mode<MODE>::self && finish) own = ld<VEC>(X + (int64_t)tk.row * ldx + c0);
+    store_row<VEC, MODE>(Y + (int64_t)tk.row * ldy + c0, acc, finish, Mode<MODE>::wrow ? rw[tk.row] : 1.0f, own, self_w);
 }
 
-// Deferred row scale of the rows that have children (MODE 1/2 only).
+// Deferred finish of the rows other work items were compressed against: row weight (MODE 1-3) or self term (MODE 4).
 template <int MODE>
-__global__ __launch_bounds__(256) void cbm_rowscale_kernel(const int32_t* __restrict__ rows, int64_t nrows, float* Y,
-                                                           int64_t ldy, const float* __restrict__ dinv, int k) {
+__global__ __launch_bounds__(256) void cbm_finish_kernel(const int32_t* __restrict__ rows, int64_t nrows,
+                                                         const float* __restrict__ X, int64_t ldx, float* Y, int64_t ldy,
+                                                         const float* __restrict__ rw, float self_w, int k) {
     const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= nrows) return;
     const int32_t x = rows[r];
-    const float s = dinv[x];
+    const float s = Mode<MODE>::wrow ? rw[x] : 1.0f;
     float* y = Y + (int64_t)x * ldy;
     for (int c = threadIdx.x & 63; c < k; c += 64) {
-        float v = y[c] * s;
-        if (MODE == 2) v = fmaxf(v, 0.0f);
+        float v = y[c];
+        if (Mode<MODE>::self) v = fmaf(self_w, X[(int64_t)x * ldx + c], v);
+        if (Mode<MODE>::wrow) v *= s;
+        if (Mode<MODE>::relu) v = fmaxf(v, 0.0f);
         y[c] = v;
     }
 }
@@ -265,6 +296,9 @@ struct LaunchCtx {
     int64_t ldy;
     int64_t ld_scratch;
     hipStream_t stream;
+    const float* cw;  // column weights (MODE 1/2)
+    const float* rw;  // row weights (MODE 1/2/3)
+    float self_w;     // MODE 4
 };
 
 template <int VEC, int LANES, int MODE, int UMAX>
@@ -276,7 +310,7 @@ void launch_level(const LaunchCtx& c, const CbmLevel& L) {
         dim3 grid((unsigned)((L.task_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
         hipLaunchKernelGGL((cbm_level_kernel<VEC, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream,
                            c.h->d_tasks + L.task_begin, L.task_count, map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy,
-                           c.h->d_scratch, c.ld_scratch, c.h->d_dinv, c.k);
+                           c.h->d_scratch, c.ld_scratch, c.cw, c.rw, c.self_w, c.k);
     }
 }
 // all segments of all split rows, one block of work items per XCD
@@ -295,7 +329,7 @@ void launch_segments(const LaunchCtx& c, const CbmLevel&) {
     dim3 grid((unsigned)(CBM_XCD * ((most + 4 * G - 1) / (4 * G))), (unsigned)ychunks);
     hipLaunchKernelGGL((cbm_level_kernel<VEC, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream, c.h->d_tasks,
                        (int64_t)c.h->tasks.size(), map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.h->d_scratch,
-                       c.ld_scratch, c.h->d_dinv, c.k);
+                       c.ld_scratch, c.cw, c.rw, c.self_w, c.k);
 }
 template <int VEC, int LANES, int MODE>
 void launch_combine(const LaunchCtx& c, const CbmLevel& L) {
@@ -303,8 +337,8 @@ void launch_combine(const LaunchCtx& c, const CbmLevel& L) {
     const int ychunks = (c.k + LANES * VEC - 1) / (LANES * VEC);
     dim3 grid((unsigned)((L.comb_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
     hipLaunchKernelGGL((cbm_combine_kernel<VEC, LANES, MODE>), grid, dim3(256), 0, c.stream,
-                       c.h->d_comb + L.comb_begin, L.comb_count, c.Y, c.ldy, c.h->d_scratch, c.ld_scratch,
-                       c.h->d_dinv, c.k);
+                       c.h->d_comb + L.comb_begin, L.comb_count, c.X, c.ldx, c.Y, c.ldy, c.h->d_scratch,
+                       c.ld_scratch, c.rw, c.self_w, c.k);
 }
 
 using LevelFn = void (*)(const LaunchCtx&, const CbmLevel&);
@@ -312,12 +346,18 @@ struct Variant {
     LevelFn level, combine, segments;
 };
 
+template <int VEC, int LANES, int MODE>
+Variant variant() {
+    return {launch_level<VEC, LANES, MODE, 8>, launch_combine<VEC, LANES, MODE>, launch_segments<VEC, LANES, MODE, 8>};
+}
 template <int VEC, int LANES>
 Variant pick_mode(int mode) {
     switch (mode) {
-        case 0: return {launch_level<VEC, LANES, 0, 8>, launch_combine<VEC, LANES, 0>, launch_segments<VEC, LANES, 0, 8>};
-        case 1: return {launch_level<VEC, LANES, 1, 8>, launch_combine<VEC, LANES, 1>, launch_segments<VEC, LANES, 1, 8>};
-        default: return {launch_level<VEC, LANES, 2, 8>, launch_combine<VEC, LANES, 2>, launch_segments<VEC, LANES, 2, 8>};
+        case 0: return variant<VEC, LANES, 0>();
+        case 1: return variant<VEC, LANES, 1>();
+        case 2: return variant<VEC, LANES, 2>();
+        case 3: return variant<VEC, LANES, 3>();
+        default: return variant<VEC, LANES, 4>();
     }
 }
 template <int VEC>
@@ -374,6 +414,7 @@ cbm_status cbm_upload(cbm_handle* h) {
     cbm_status st = CBM_OK;
     if ((st = up(&h->d_tasks, h->tasks)) != CBM_OK || (st = up(&h->d_comb, h->comb)) != CBM_OK ||
         (st = up(&h->d_stream, h->stream)) != CBM_OK || (st = up(&h->d_dinv, h->dinv)) != CBM_OK ||
+        (st = up(&h->d_rinv, h->rinv)) != CBM_OK ||
         (st = up(&h->d_internal, h->internal_rows)) != CBM_OK) {
         cbm_release_device(h);
         if (cur != dev) hipSetDevice(cur);
@@ -391,11 +432,13 @@ void cbm_release_device(cbm_handle* h) {
     if (h->d_comb) hipFree(h->d_comb);
     if (h->d_stream) hipFree(h->d_stream);
     if (h->d_dinv) hipFree(h->d_dinv);
+    if (h->d_rinv) hipFree(h->d_rinv);
     if (h->d_internal) hipFree(h->d_internal);
     if (h->d_scratch) hipFree(h->d_scratch);
     h->d_tasks = h->d_comb = nullptr;
     h->d_stream = nullptr;
     h->d_dinv = nullptr;
+    h->d_rinv = nullptr;
     h->d_internal = nullptr;
     h->d_scratch = nullptr;
     h->scratch_k = 0;
@@ -403,7 +446,7 @@ void cbm_release_device(cbm_handle* h) {
 }
 
 cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
-                              CbmEpilogue epi, void* stream_) {
+                              CbmEpilogue epi, float self_weight, void* stream_) {
     hipStream_t stream = (hipStream_t)stream_;
     int cur = -1;
     HIP_TRY(hipGetDevice(&cur), CBM_ERR_HIP);
@@ -435,9 +478,11 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
         h->prof_events.clear();
         h->prof_records.clear();
     }
-    const LaunchCtx ctx{h, X, ldx, k, Y, ldy, ld_scratch, stream};
+    const bool wcol = mode == 1 || mode == 2, wrow = wcol || mode == 3;
+    const LaunchCtx ctx{h, X, ldx, k, Y, ldy, ld_scratch, stream, h->d_dinv, mode == 3 ? h->d_rinv : h->d_dinv, self_weight};
     const int64_t rowb = 4 * (int64_t)k;
-    const int64_t per_delta = rowb + 4 + (mode != 0 ? 4 : 0);
+    const int64_t per_delta = rowb + 4 + (wcol ? 4 : 0);
+    const int64_t per_row = rowb + 4 + (wrow ? 4 : 0) + (mode == 4 ? rowb : 0);  // Y write, marker, weight, own X row
     if (h->num_slots > 0) {
         cbm_launch_record rec{};
         rec.kind = 1;
@@ -458,8 +503,7 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
             rec.deltas = L.deltas;
             // per delta: one X row + its entry (+ d^-1/2); per row: one Y write + its marker entry (+ d^-1/2);
             // per work item with a parent: the parent's row
-            rec.algorithmic_bytes = L.deltas * per_delta + (L.rows_written + L.parent_reads) * rowb +
-                                    (mode != 0 ? 8 : 4) * L.rows_written;
+            rec.algorithmic_bytes = L.deltas * per_delta + L.rows_written * per_row + L.parent_reads * rowb;
             ProfScope ps(h, stream, rec);
             var.level(ctx, L);
         }
@@ -469,7 +513,7 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
             rec.level = (int32_t)l + 1;
             rec.tasks = L.comb_count;
             // split rows: the Y write and the parent read belong to the method, the partial sums do not
-            rec.algorithmic_bytes = (L.comb_parent_reads + L.comb_count) * rowb + (mode != 0 ? 8 : 4) * L.comb_count;
+            rec.algorithmic_bytes = L.comb_parent_reads * rowb + L.comb_count * per_row;
             ProfScope ps(h, stream, rec);
             var.combine(ctx, L);
         }
@@ -479,15 +523,12 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
         cbm_launch_record rec{};
         rec.kind = 3;
         rec.tasks = nr;
-        rec.algorithmic_bytes = 0;  // the deferred row scale is overhead of this implementation
+        rec.algorithmic_bytes = 0;  // the deferred finish is overhead of this implementation
         ProfScope ps(h, stream, rec);
         dim3 grid((unsigned)((nr + 3) / 4));
-        if (mode == 1)
-            hipLaunchKernelGGL(cbm_rowscale_kernel<1>, grid, dim3(256), 0, stream, h->d_internal, nr, Y, ldy,
-                               h->d_dinv, k);
-        else
-            hipLaunchKernelGGL(cbm_rowscale_kernel<2>, grid, dim3(256), 0, stream, h->d_internal, nr, Y, ldy,
-                               h->d_dinv, k);
+        auto fin = mode == 1 ? cbm_finish_kernel<1> : mode == 2 ? cbm_finish_kernel<2> : mode == 3 ? cbm_finish_kernel<3>
+                                                                                                   : cbm_finish_kernel<4>;
+        hipLaunchKernelGGL(fin, grid, dim3(256), 0, stream, h->d_internal, nr, X, ldx, Y, ldy, ctx.rw, self_weight, k);
     }
     HIP_TRY(hipGetLastError(), CBM_ERR_HIP);
     return CBM_OK;

@@ -164,6 +164,69 @@ def test_split_rows_and_empty_rows(env):
                                 orc.spmm_csr_normalized(rowptr, colidx, Xg)) <= TOL
 
 
+@pytest.mark.parametrize("name", wl.CONFIGS)
+@pytest.mark.parametrize("k", [3, 64, 128, 500])
+def test_mean_and_gin_aggregators(env, graphs, name, k):
+    """The GraphSAGE mean and the GIN sum as epilogues of the same kernels: Gaussian features to 1e-5,
+    GIN on integer features with an exactly representable 1 + eps bit for bit; both a deep tree
+    (deferred finish of internal rows) and the handle built with self loops (M = A v I)."""
+    torch, cbm = env
+    g = graphs[name]
+    X = wl.gaussian_features(g.n, k, g.meta["seed"])
+    Xi = wl.integer_features(g.n, k, g.meta["seed"])
+    Xd, Xid = torch.from_numpy(X).cuda(), torch.from_numpy(Xi).cuda()
+    for opts in (dict(max_depth=16), dict(alpha=2), dict(max_depth=16, add_self_loops=True)):
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, **opts)
+        if opts.get("add_self_loops"):
+            R = orc.adjacency_lists(g.n, g.rowptr, g.colidx, add_self_loops=True)[1:]
+            rowptr, colidx = _csr(R)
+        else:
+            rowptr, colidx = g.rowptr, g.colidx
+        got = _run(env, "cbm_spmm_mean", h, X, g.n)
+        assert row_scaled_error(got, orc.spmm_csr_mean(rowptr, colidx, X)) <= TOL
+        Y = torch.full((g.n, k), float("nan"), device="cuda")
+        cbm.cbm_spmm_gin(h, 0.25, Xd, Y)
+        ref = orc.spmm_csr_gin(rowptr, colidx, X, 0.25)
+        assert row_scaled_error(Y.cpu().numpy(), ref) <= TOL
+        cbm.cbm_spmm_gin(h, 1.0, Xid, Y.fill_(float("nan")))
+        ref = orc.spmm_csr_gin(rowptr, colidx, Xi, 1.0)
+        assert np.abs(ref).max() < 2 ** 24
+        assert np.array_equal(Y.cpu().numpy().astype(np.float64), ref)
+        cbm.cbm_free(h)
+
+
+def test_mean_and_gin_on_split_and_empty_rows(env):
+    torch, cbm = env
+    rng = np.random.default_rng(1)
+    n = 5000
+    dense_row = sorted(rng.choice(n, size=2048, replace=False).tolist())   # 2048 entries: 1/2048 is exact
+    near = sorted(set(dense_row[:2000]) | {5, 7})
+    rows = [dense_row, near, [], [1, 2, 3, 4]] + [[]] * 2
+    rows += [sorted(rng.choice(n, size=int(s), replace=False).tolist()) for s in rng.integers(0, 40, size=n - len(rows))]
+    rowptr, colidx = _csr(rows)
+    h = cbm.cbm_build(n, n, rowptr, colidx, max_depth=16)
+    assert cbm.cbm_stats(h)["num_split_rows"] >= 1
+    for k in (4, 100, 256):
+        Xi = wl.integer_features(n, k, 3)
+        got = _run(env, "cbm_spmm_mean", h, Xi, n).astype(np.float64)
+        ref = orc.spmm_csr_mean(rowptr, colidx, Xi)
+        assert np.array_equal(got[[0, 2, 3, 4, 5]], ref[[0, 2, 3, 4, 5]])      # power-of-two and empty rows: exact
+        assert row_scaled_error(got, ref) <= TOL
+        Y = torch.full((n, k), float("nan"), device="cuda")
+        cbm.cbm_spmm_gin(h, -0.5, torch.from_numpy(2 * Xi).cuda(), Y)          # (1 + eps) * even integer: exact
+        assert np.array_equal(Y.cpu().numpy().astype(np.float64), orc.spmm_csr_gin(rowptr, colidx, 2 * Xi, -0.5))
+    # rectangular handle: the mean is defined, GIN is not
+    m2, n2 = 300, 700
+    rows = [sorted(rng.choice(n2, size=int(s), replace=False).tolist()) for s in rng.integers(0, 30, size=m2)]
+    rowptr, colidx = _csr(rows)
+    h = cbm.cbm_build(m2, n2, rowptr, colidx, max_depth=16)
+    Xg = wl.gaussian_features(n2, 24, 5)
+    assert row_scaled_error(_run(env, "cbm_spmm_mean", h, Xg, m2), orc.spmm_csr_mean(rowptr, colidx, Xg)) <= TOL
+    with pytest.raises(cbm.CbmError) as e:
+        cbm.cbm_spmm_gin(h, 0.0, torch.from_numpy(Xg).cuda(), torch.empty((m2, 24), device="cuda"))
+    assert e.value.status == 6
+
+
 def test_degenerate_shapes(env):
     torch, cbm = env
     # empty matrix

@@ -329,3 +329,42 @@ def test_gcn2_against_dense_definition_and_closed_form():
     X, W0, W1 = np.abs(X[:6]), np.abs(W0), W1
     want = np.tile(X.astype(np.float64).mean(0) @ W0.astype(np.float64) @ W1.astype(np.float64), (6, 1))
     np.testing.assert_allclose(orc.gcn2(rowptr, colidx, X, W0, W1), want, rtol=1e-12)
+
+
+# ----------------------------- mean and GIN aggregators -------------------- #
+def test_mean_and_gin_closed_forms():
+    # complete graph without self loops: mean over the other n-1 rows; GIN = column sum + eps x_i
+    n, eps = 7, 0.25
+    rowptr, colidx = _graph_csr(n, itertools.combinations(range(n), 2))
+    X = np.random.default_rng(2).standard_normal((n, 4))
+    tot = X.sum(axis=0)
+    np.testing.assert_allclose(orc.spmm_csr_mean(rowptr, colidx, X), (tot[None, :] - X) / (n - 1), rtol=1e-13)
+    np.testing.assert_allclose(orc.spmm_csr_gin(rowptr, colidx, X, eps), tot[None, :] + eps * X, rtol=1e-13,
+                               atol=1e-14)
+    # cycle: two-point average; GIN with eps = -1 is the plain product
+    n = 9
+    rowptr, colidx = _graph_csr(n, [(i, (i + 1) % n) for i in range(n)])
+    X = np.random.default_rng(3).integers(-8, 9, size=(n, 3)).astype(np.float64)
+    assert np.array_equal(orc.spmm_csr_mean(rowptr, colidx, X), (np.roll(X, 1, 0) + np.roll(X, -1, 0)) / 2.0)
+    assert np.array_equal(orc.spmm_csr_gin(rowptr, colidx, X, -1.0), orc.spmm_csr(rowptr, colidx, X))
+    assert np.array_equal(orc.spmm_csr_gin(rowptr, colidx, X, 1.0), np.roll(X, 1, 0) + np.roll(X, -1, 0) + 2 * X)
+
+
+def test_mean_and_gin_against_dense_definition():
+    rng = np.random.default_rng(12)
+    n = 21
+    rows = _random_rows(rng, n, n, 0.25)
+    rows[4] = []                                    # an empty row: mean gives zeros, GIN gives (1+eps) x_i
+    rowptr, colidx = _csr(rows, n)
+    A = orc.dense_from_csr(n, n, rowptr, colidx)
+    X = rng.standard_normal((n, 5))
+    deg = A.sum(axis=1)
+    Dinv = np.diag([1.0 / d if d else 0.0 for d in deg])
+    np.testing.assert_allclose(orc.spmm_csr_mean(rowptr, colidx, X), Dinv @ A @ X, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(orc.spmm_csr_gin(rowptr, colidx, X, 0.5), (A + 1.5 * np.eye(n)) @ X, rtol=1e-13,
+                               atol=1e-14)
+    assert not orc.spmm_csr_mean(rowptr, colidx, X)[4].any()
+    sub = [3, 4, 17]
+    assert np.array_equal(orc.spmm_csr_mean(rowptr, colidx, X, rows=sub), orc.spmm_csr_mean(rowptr, colidx, X)[sub])
+    assert np.array_equal(orc.spmm_csr_gin(rowptr, colidx, X, 0.5, rows=sub),
+                          orc.spmm_csr_gin(rowptr, colidx, X, 0.5)[sub])
