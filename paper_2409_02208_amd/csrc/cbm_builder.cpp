@@ -150,7 +150,7 @@ struct Builder {
     bool is_split(int64_t x) const { return dlen(x) > split_min; }
     void tree_index();
     double plan(int64_t path_max, int32_t* nrounds_out);
-    double last_round_us = 0.0;
+    double last_round_us = 0.0, last_round_bytes_us = 0.0;  // of the last round: modelled time; its bandwidth term alone
     bool prune_last_round(int64_t path_max);
     double csr_cost() const;
     cbm_status emit(int32_t nrounds);
@@ -660,6 +660,7 @@ double Builder::plan(int64_t path_max, int32_t* nrounds_out) {
         if (comb[r] > 0) round_us += kLaunchUs + comb[r] * kRefRowBytes / kBytesPerUs;
         us += round_us;
         last_round_us = round_us;
+        last_round_bytes_us = (entries[r] + rows[r] + comb[r]) * kRefRowBytes / kBytesPerUs;
     }
     if (fixup && h->square_self_loops) us += kLaunchUs;
     return us;
@@ -668,7 +669,9 @@ double Builder::plan(int64_t path_max, int32_t* nrounds_out) {
 // The paper prunes compression opportunities that do not pay for their overhead (Section 2.2, "Edge
 // Pruning").  Here the overhead that matters is a whole dependent launch: if storing the heads of the LAST
 // round in full costs less (a few more gathered rows in round 1) than that round's launch and latency, do
-// so; the round disappears.  Returns true if the tree changed.
+// so; the round disappears.  The round's gathered rows do not: its paths move to round 1 with their
+// entries, so what is saved is the launch, the latency of its longest path where that exceeds the
+// bandwidth term, and one parent-row read per head.  Returns true if the tree changed.
 bool Builder::prune_last_round(int64_t path_max) {
     int32_t nr = 0;
     plan(path_max, &nr);
@@ -682,10 +685,11 @@ bool Builder::prune_last_round(int64_t path_max) {
         heads.push_back((int32_t)x);
         extra += rlen(x) - dlen(x);
     }
-    if (last_round_us <= extra * kRefRowBytes / kBytesPerUs) return false;
+    const double saved = last_round_us - last_round_bytes_us + heads.size() * kRefRowBytes / kBytesPerUs;
+    if (saved <= extra * kRefRowBytes / kBytesPerUs) return false;
     if (verbose)
-        std::fprintf(stderr, "[cbm_build] round %d (%zu heads, model %.1f us) dropped: heads stored in full, +%ld deltas\n", nr,
-                     heads.size(), last_round_us, (long)extra);
+        std::fprintf(stderr, "[cbm_build] round %d (%zu heads, saves %.1f us) dropped: heads stored in full, +%ld deltas\n", nr,
+                     heads.size(), saved, (long)extra);
     std::vector<int64_t> len(m);
     for (int64_t x = 0; x < m; ++x) len[x] = dlen(x);
     for (int32_t x : heads) {

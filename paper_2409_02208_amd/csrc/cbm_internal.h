@@ -74,6 +74,7 @@ struct cbm_handle {
     uint32_t* d_stream = nullptr;
     float* d_dinv = nullptr;
     float* d_rinv = nullptr;
+    float* d_wstream = nullptr;  // weight of every stream entry (normalised product), computed on the device at upload
     int32_t* d_internal = nullptr;
     mutable float* d_scratch = nullptr;  // num_slots x scratch_k floats, sized on first use
     mutable int64_t scratch_k = 0;

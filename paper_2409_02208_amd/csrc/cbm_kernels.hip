@@ -105,7 +105,9 @@ __device__ __forceinline__ void store_row(float* dst, Vec<VEC> acc, bool finish,
 // load, two chunks ahead; their d^-1/2 weights one chunk ahead) and broadcast inside the group.
 // X rows are loaded in batches of U; two batches ping-pong so that the loads of batch b+1 are in
 // flight while batch b is accumulated: a long path is a chain of dependent adds, but never a chain
-// of dependent loads.
+// of dependent loads.  Two builds of every variant: batches of 8 rows at 4 waves per SIMD for
+// launches with few, long work items (the loads in flight come from inside each item), batches
+// of 4 at 6 or more waves per SIMD for launches with many work items (they come from occupancy).
 // Segment launches map workgroups to work items per XCD: workgroup b runs on XCD b mod 8 and takes
 // its items from that XCD's block of the task list (the segments of one column range of X).
 struct CbmSegMap {
@@ -114,13 +116,21 @@ struct CbmSegMap {
     int use;
 };
 
+// Waves per SIMD the register allocation is held to: 4 with batches of 8 rows, 6 with batches of 4 --
+// one less for the few variants that would otherwise spill registers.
+constexpr int level_min_waves(int vec, int lanes, int mode, int umax) {
+    const bool weighted = mode >= 1 && mode <= 3;
+    if (umax >= 8) return (vec == 4 && lanes == 16 && weighted) ? 3 : 4;
+    return (vec == 4 && lanes <= 8 && weighted) ? 5 : 6;
+}
+
 template <int VEC, int LANES, int MODE, int UMAX>
-__global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restrict__ tasks, int64_t ntasks,
+__global__ __launch_bounds__(256, level_min_waves(VEC, LANES, MODE, UMAX)) void cbm_level_kernel(const CbmTask* __restrict__ tasks, int64_t ntasks,
                                                         const CbmSegMap map,
                                                         const uint32_t* __restrict__ stream,
                                                         const float* __restrict__ X, int64_t ldx, float* Y,
                                                         int64_t ldy, float* scratch, int64_t ld_scratch,
-                                                        const float* __restrict__ cw, const float* __restrict__ rw,
+                                                        const float* __restrict__ ws, const float* __restrict__ rw,
                                                         float self_w, int k) {
     using M = Mode<MODE>;
     constexpr int G = 64 / LANES;                  // work items per wave
@@ -155,38 +165,39 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
         const uint32_t idx = (uint32_t)chunk * LANES + sl;
         return idx < len ? __builtin_nontemporal_load(es + idx) : 0u;  // read once: keep it out of the way of X
     };
+    const float* wes = ws + tk.start;
     auto load_w = [&](uint32_t e, int chunk) -> float {  // signed column weight of a delta, row weight of a marker
         if (!M::weights) return 0.0f;
         const uint32_t idx = (uint32_t)chunk * LANES + sl;
         if (idx >= len) return 0.0f;
-        if (e & CBM_ENTRY_MARK) return M::wrow ? rw[e & CBM_ENTRY_INDEX_MASK] : 0.0f;
-        if (!M::wcol) return 0.0f;
-        const float w = cw[e & CBM_ENTRY_INDEX_MASK];
-        return (e & CBM_DELTA_MINUS) ? -w : w;
+        if (M::wcol) return __builtin_nontemporal_load(wes + idx);  // stored per entry, beside the stream
+        return (e & CBM_ENTRY_MARK) ? rw[e & CBM_ENTRY_INDEX_MASK] : 0.0f;
     };
     uint32_t e0 = load_e(0), e1 = load_e(1), e2 = load_e(2);
     float w0 = load_w(e0, 0), w1 = load_w(e1, 1);
+    float wprev = 0.0f;  // weights of the chunk before the current one: its last batch is consumed after the rotation
+    int cur = 0;         // chunk whose entries are in e0 / w0
 
     struct Batch {
         Vec<VEC> x[U];
         uint32_t e[U];
-        float w[U];
     };
     const int nb = (int)((len + U - 1) / U);
     auto fetch = [&](Batch& S, int b) {
         if (b > 0 && b % BPC == 0) {  // batch b opens the next chunk: rotate the entry pipeline
             const int chunk = b / BPC;
             e0 = e1;
+            wprev = w0;
             w0 = w1;
             e1 = e2;
             e2 = load_e(chunk + 2);
             w1 = load_w(e1, chunk + 1);
+            cur = chunk;
         }
         const int off = (b % BPC) * U;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             S.e[u] = (uint32_t)__shfl((int)e0, off + u, LANES);
-            S.w[u] = M::weights ? __shfl(w0, off + u, LANES) : 0.0f;
             // a delta gathers its column's row of X; in MODE 4 a marker gathers the row's own X row
             const bool gather = !(S.e[u] & CBM_ENTRY_MARK) ||
                                 (M::self && !(S.e[u] & CBM_ENTRY_INTERNAL));
@@ -198,16 +209,20 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
             }
         }
     };
-    auto consume = [&](const Batch& S) {
+    auto consume = [&](const Batch& S, int b) {
+        // weights are broadcast here, not at fetch time: one register per lane instead of U per batch
+        const float wsrc = (b / BPC == cur) ? w0 : wprev;
+        const int off = (b % BPC) * U;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
+            const float w = M::weights ? __shfl(wsrc, off + u, LANES) : 0.0f;
             if (S.e[u] & CBM_ENTRY_MARK) {
                 if (colok)
                     store_row<VEC, MODE>(Y + (int64_t)(S.e[u] & CBM_ENTRY_INDEX_MASK) * ldy + c0, acc,
-                                         !(S.e[u] & CBM_ENTRY_INTERNAL), S.w[u], S.x[u], self_w);
+                                         !(S.e[u] & CBM_ENTRY_INTERNAL), w, S.x[u], self_w);
             } else if (M::wcol) {
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(S.w[u], S.x[u].v[c], acc.v[c]);
+                for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(w, S.x[u].v[c], acc.v[c]);
             } else {
                 const uint32_t sgn = S.e[u] & CBM_DELTA_MINUS;
 #pragma unroll
@@ -219,9 +234,9 @@ __global__ __launch_bounds__(256) void cbm_level_kernel(const CbmTask* __restric
     if (nb > 0) fetch(A, 0);
     for (int b = 0; b < nb; b += 2) {
         if (b + 1 < nb) fetch(B, b + 1);
-        consume(A);
+        consume(A, b);
         if (b + 2 < nb) fetch(A, b + 2);
-        if (b + 1 < nb) consume(B);
+        if (b + 1 < nb) consume(B, b + 1);
     }
     if ((tk.len_flags & CBM_TASK_SEGMENT) && colok) st_stream<VEC>(scratch + (int64_t)tk.row * ld_scratch + c0, acc);
 }
@@ -287,6 +302,21 @@ __global__ __launch_bounds__(256) void cbm_finish_kernel(const int32_t* __restri
     }
 }
 
+// Weight of every stream entry for the normalised product: +-d_j^-1/2 for a delta on column j, d_x^-1/2 for the
+// marker of row x.  Stored once per handle so that the product kernel reads weights as it reads entries --
+// coalesced -- instead of gathering one word per delta.
+__global__ __launch_bounds__(256) void cbm_entry_weights_kernel(const uint32_t* __restrict__ stream, int64_t nent,
+                                                                const float* __restrict__ dinv, float* __restrict__ w) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= nent) return;
+    const uint32_t e = stream[i];
+    const float d = dinv[e & CBM_ENTRY_INDEX_MASK];
+    w[i] = (!(e & CBM_ENTRY_MARK) && (e & CBM_DELTA_MINUS)) ? -d : d;
+}
+
+// 256 CUs x 4 SIMDs x 8 waves = 8192 resident waves at most; from eight times that on, a launch is "many waves"
+constexpr int64_t kManyWavesDefault = 65536;
+
 struct LaunchCtx {
     const cbm_handle* h;
     const float* X;
@@ -296,7 +326,7 @@ struct LaunchCtx {
     int64_t ldy;
     int64_t ld_scratch;
     hipStream_t stream;
-    const float* cw;  // column weights (MODE 1/2)
+    const float* ws;  // per-entry weights of the stream (MODE 1/2)
     const float* rw;  // row weights (MODE 1/2/3)
     float self_w;     // MODE 4
 };
@@ -310,7 +340,7 @@ void launch_level(const LaunchCtx& c, const CbmLevel& L) {
         dim3 grid((unsigned)((L.task_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
         hipLaunchKernelGGL((cbm_level_kernel<VEC, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream,
                            c.h->d_tasks + L.task_begin, L.task_count, map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy,
-                           c.h->d_scratch, c.ld_scratch, c.cw, c.rw, c.self_w, c.k);
+                           c.h->d_scratch, c.ld_scratch, c.ws, c.rw, c.self_w, c.k);
     }
 }
 // all segments of all split rows, one block of work items per XCD
@@ -329,7 +359,7 @@ void launch_segments(const LaunchCtx& c, const CbmLevel&) {
     dim3 grid((unsigned)(CBM_XCD * ((most + 4 * G - 1) / (4 * G))), (unsigned)ychunks);
     hipLaunchKernelGGL((cbm_level_kernel<VEC, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream, c.h->d_tasks,
                        (int64_t)c.h->tasks.size(), map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.h->d_scratch,
-                       c.ld_scratch, c.cw, c.rw, c.self_w, c.k);
+                       c.ld_scratch, c.ws, c.rw, c.self_w, c.k);
 }
 template <int VEC, int LANES, int MODE>
 void launch_combine(const LaunchCtx& c, const CbmLevel& L) {
@@ -343,12 +373,15 @@ void launch_combine(const LaunchCtx& c, const CbmLevel& L) {
 
 using LevelFn = void (*)(const LaunchCtx&, const CbmLevel&);
 struct Variant {
-    LevelFn level, combine, segments;
+    LevelFn level, combine, segments;  // batches of 8 rows
+    LevelFn level_many, segments_many;  // batches of 4 rows, higher occupancy: for launches of many work items
+    int group;                          // work items per wave
 };
 
 template <int VEC, int LANES, int MODE>
 Variant variant() {
-    return {launch_level<VEC, LANES, MODE, 8>, launch_combine<VEC, LANES, MODE>, launch_segments<VEC, LANES, MODE, 8>};
+    return {launch_level<VEC, LANES, MODE, 8>,    launch_combine<VEC, LANES, MODE>, launch_segments<VEC, LANES, MODE, 8>,
+            launch_level<VEC, LANES, MODE, 4>,    launch_segments<VEC, LANES, MODE, 4>, 64 / LANES};
 }
 template <int VEC, int LANES>
 Variant pick_mode(int mode) {
@@ -420,6 +453,22 @@ cbm_status cbm_upload(cbm_handle* h) {
         if (cur != dev) hipSetDevice(cur);
         return st;
     }
+    if (h->square_self_loops && !h->stream.empty()) {
+        const int64_t nent = (int64_t)h->stream.size();
+        hipError_t e = hipMalloc((void**)&h->d_wstream, nent * sizeof(float));
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(cbm_entry_weights_kernel, dim3((unsigned)((nent + 255) / 256)), dim3(256), 0, 0, h->d_stream,
+                               nent, h->d_dinv, h->d_wstream);
+            e = hipGetLastError();
+            if (e == hipSuccess) e = hipDeviceSynchronize();
+        }
+        if (e != hipSuccess) {
+            cbm_set_error_detail("entry weights", hipGetErrorString(e));
+            cbm_release_device(h);
+            if (cur != dev) hipSetDevice(cur);
+            return CBM_ERR_HIP;
+        }
+    }
     h->on_device = true;
     if (cur != dev) hipSetDevice(cur);
     return CBM_OK;
@@ -433,12 +482,14 @@ void cbm_release_device(cbm_handle* h) {
     if (h->d_stream) hipFree(h->d_stream);
     if (h->d_dinv) hipFree(h->d_dinv);
     if (h->d_rinv) hipFree(h->d_rinv);
+    if (h->d_wstream) hipFree(h->d_wstream);
     if (h->d_internal) hipFree(h->d_internal);
     if (h->d_scratch) hipFree(h->d_scratch);
     h->d_tasks = h->d_comb = nullptr;
     h->d_stream = nullptr;
     h->d_dinv = nullptr;
     h->d_rinv = nullptr;
+    h->d_wstream = nullptr;
     h->d_internal = nullptr;
     h->d_scratch = nullptr;
     h->scratch_k = 0;
@@ -478,8 +529,15 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
         h->prof_events.clear();
         h->prof_records.clear();
     }
+    // a launch of this many waves or more hides latency by occupancy: small batches, more waves per SIMD
+    static const int64_t many_waves = [] {
+        const char* e = std::getenv("CBM_MANY_WAVES");
+        return e ? std::atoll(e) : (int64_t)kManyWavesDefault;
+    }();
+    const int64_t ychunks = ((int64_t)k + lanes * vec - 1) / (lanes * vec);
+    auto many = [&](int64_t items) { return items / var.group * ychunks >= many_waves; };
     const bool wcol = mode == 1 || mode == 2, wrow = wcol || mode == 3;
-    const LaunchCtx ctx{h, X, ldx, k, Y, ldy, ld_scratch, stream, h->d_dinv, mode == 3 ? h->d_rinv : h->d_dinv, self_weight};
+    const LaunchCtx ctx{h, X, ldx, k, Y, ldy, ld_scratch, stream, h->d_wstream, mode == 3 ? h->d_rinv : h->d_dinv, self_weight};
     const int64_t rowb = 4 * (int64_t)k;
     const int64_t per_delta = rowb + 4 + (wcol ? 4 : 0);
     const int64_t per_row = rowb + 4 + (wrow ? 4 : 0) + (mode == 4 ? rowb : 0);  // Y write, marker, weight, own X row
@@ -491,7 +549,7 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
         // the method's bytes only: the partial sums of split rows are this implementation's overhead
         rec.algorithmic_bytes = h->seg_deltas * per_delta;
         ProfScope ps(h, stream, rec);
-        var.segments(ctx, CbmLevel{});
+        (many(h->num_slots) ? var.segments_many : var.segments)(ctx, CbmLevel{});
     }
     for (size_t l = 0; l < h->levels.size(); ++l) {
         const CbmLevel& L = h->levels[l];
@@ -505,7 +563,7 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
             // per work item with a parent: the parent's row
             rec.algorithmic_bytes = L.deltas * per_delta + L.rows_written * per_row + L.parent_reads * rowb;
             ProfScope ps(h, stream, rec);
-            var.level(ctx, L);
+            (many(L.task_count) ? var.level_many : var.level)(ctx, L);
         }
         if (L.comb_count > 0) {
             cbm_launch_record rec{};
