@@ -46,6 +46,12 @@ typedef enum {
                                   ignored.  With hub_cap = max_candidates = -1 the
                                   candidate digraph is the whole pruned distance graph. */
 
+#define CBM_FLAG_DEVICE_BUILD 4u /* run the builder's candidate search (which rows share columns
+                                    with which, the pattern of A A^T) on the GPU instead of the
+                                    host threads; the chain of compression is the same.  Needs
+                                    1 <= max_candidates <= 16 (the default qualifies); not with
+                                    CBM_FLAG_HOST_ONLY.                                         */
+
 /*
  * Build options.  A NULL pointer means all zeros, i.e. the defaults below.
  *

@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcbm.so")
-SOURCES = ["cbm_api.cpp", "cbm_builder.cpp", "cbm_kernels.hip", "cbm_gemm.hip"]
+SOURCES = ["cbm_api.cpp", "cbm_builder.cpp", "cbm_kernels.hip", "cbm_gemm.hip", "cbm_build_kernels.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-result", "-Wno-unused-value"]

@@ -1,0 +1,350 @@
+// Candidate search of the builder on the GPU.
+//
+// The compression tree is chosen among "candidate" edges (y, x): rows y that share columns with
+// row x, ranked by the Hamming distance of Lemma 2.1, w(y,x) = nnz(a_x) + nnz(a_y) - 2 |a_x n a_y|.
+// Finding them is the pattern of the sparse product A A^T: for every column j of row x, every row y
+// of column j shares one more column with x.  One workgroup owns one row at a time and counts in a
+// dense array of its own (one counter per row of the matrix: the chip's memory is large enough to give
+// every resident workgroup such an array), then scores the rows it touched, keeps the best few and
+// settles them by exact list intersection where columns were skipped as hubs.  The selection rule and
+// the tie-breaks are those of the host search, so both produce the same candidate set.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <vector>
+
+#include "cbm_internal.h"
+
+namespace {
+
+constexpr int kCandMax = 16;          // most candidates kept per row
+constexpr int kSelMax = 2 * kCandMax;  // most candidates settled by exact intersection
+
+struct CandArgs {
+    int64_t m;
+    const int64_t* rowptr;  // the compressed matrix (A or A v I), CSR
+    const int32_t* colidx;
+    const int64_t* tptr;  // its transpose: rows holding each column
+    const int32_t* trow;
+    const int32_t* order;  // rows in the order workgroups take them (heaviest first)
+    int64_t hub_cap;       // columns held by more rows than this are not expanded (< 0: no cap)
+    int64_t min_saving;    // a candidate must save at least this many deltas
+    int32_t keep;          // candidates kept per row, <= kCandMax
+    unsigned long long* next;  // work queue: index into order[] of the next row
+    uint32_t* cnt;             // [workgroup][m] shared-column counters, all zero between rows
+    int32_t* touched;          // [workgroup][m] rows with a non-zero counter
+    unsigned long long* pass;  // [workgroup][m] keys of the rows that may save enough
+    int32_t* out_n;            // [m] candidates found
+    int32_t* out_y;            // [m][keep] candidate parents
+    int32_t* out_w;            // [m][keep] their distance w(y,x)
+};
+
+// larger key = better candidate: higher saving first, then the smaller row index
+__device__ __forceinline__ unsigned long long make_key(int64_t saving, int32_t y) {
+    return ((unsigned long long)saving << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)y);
+}
+__device__ __forceinline__ int32_t key_row(unsigned long long key) { return (int32_t)(0xFFFFFFFFu - (uint32_t)key); }
+
+__device__ __forceinline__ unsigned long long wave_max(unsigned long long v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)v, off, 64);
+        const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(v >> 32), off, 64);
+        const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+        v = o > v ? o : v;
+    }
+    return v;
+}
+__device__ __forceinline__ int64_t wave_sum(int64_t v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)v, off, 64);
+        const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)((uint64_t)v >> 32), off, 64);
+        v += (int64_t)(((uint64_t)hi << 32) | lo);
+    }
+    return v;
+}
+
+__global__ __launch_bounds__(256) void cbm_candidates_kernel(const CandArgs a) {
+    __shared__ unsigned long long s_row;
+    __shared__ unsigned s_ntouched, s_npass, s_nhub;
+    __shared__ unsigned long long s_sel[kSelMax];
+    __shared__ long long s_saving[kSelMax];
+    __shared__ unsigned long long s_red[4];
+    uint32_t* cnt = a.cnt + (size_t)blockIdx.x * a.m;
+    int32_t* touched = a.touched + (size_t)blockIdx.x * a.m;
+    unsigned long long* pass = a.pass + (size_t)blockIdx.x * a.m;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    for (;;) {
+        __syncthreads();  // everyone is done with the shared state of the previous row
+        if (tid == 0) {
+            s_row = atomicAdd(a.next, 1ull);
+            s_ntouched = 0;
+            s_npass = 0;
+            s_nhub = 0;
+        }
+        __syncthreads();
+        if (s_row >= (unsigned long long)a.m) return;  // the queue only grows: every workgroup gets here
+        const int32_t x = a.order[s_row];
+        const int64_t xb = a.rowptr[x], nx = a.rowptr[x + 1] - xb;
+        if (nx < 1) {
+            if (tid == 0) a.out_n[x] = 0;
+            continue;
+        }
+
+        // 1. count shared columns: a column per group of 16 lanes, the column's rows over the lanes
+        const int grp = tid >> 4, gl = tid & 15;
+        unsigned myhub = 0;
+        for (int64_t p = grp; p < nx; p += 16) {
+            const int32_t j = a.colidx[xb + p];
+            const int64_t tb = a.tptr[j], deg = a.tptr[j + 1] - tb;
+            if (a.hub_cap >= 0 && deg > a.hub_cap) {  // a hub column: too many rows to expand
+                if (gl == 0) ++myhub;
+                continue;
+            }
+            for (int64_t q = gl; q < deg; q += 16) {
+                const int32_t y = a.trow[tb + q];
+                if (atomicAdd(&cnt[y], 1u) == 0u) touched[atomicAdd(&s_ntouched, 1u)] = y;
+            }
+        }
+        if (myhub) atomicAdd(&s_nhub, myhub);
+        __syncthreads();
+        const unsigned ntouched = s_ntouched;
+        const int64_t nhub = s_nhub;
+
+        // 2. score what was touched (upper bound of the saving where hub columns were skipped); the exchange
+        //    reads the counter where the atomics counted it and leaves it zero for the next row
+        for (unsigned i = tid; i < ntouched; i += 256) {
+            const int32_t y = touched[i];
+            const int64_t shared = (int64_t)atomicExch(&cnt[y], 0u);
+            if (y == x) continue;
+            const int64_t ny = a.rowptr[y + 1] - a.rowptr[y];
+            const int64_t room = (ny < nx ? ny : nx) - shared;  // columns the two rows could still share among the hubs
+            const int64_t most = shared + (nhub < room ? nhub : room);
+            const int64_t ub = 2 * most - ny;  // saving = nnz(a_x) - w(y,x) = 2 |a_x n a_y| - nnz(a_y)
+            if (ub >= a.min_saving) pass[atomicAdd(&s_npass, 1u)] = make_key(ub, y);
+        }
+        __syncthreads();
+        const unsigned npass = s_npass;
+        if (npass == 0) {
+            if (tid == 0) a.out_n[x] = 0;
+            continue;
+        }
+
+        // 3. the best `nsel` of them: all, or repeated maximum below the previous maximum (keys are distinct)
+        const unsigned want = (unsigned)(nhub > 0 ? 2 * a.keep : a.keep);
+        const unsigned nsel = npass < want ? npass : want;
+        if (npass <= nsel) {
+            for (unsigned i = tid; i < npass; i += 256) s_sel[i] = pass[i];
+        } else {
+            unsigned long long bound = ~0ull;
+            for (unsigned r = 0; r < nsel; ++r) {
+                unsigned long long best = 0;
+                for (unsigned i = tid; i < npass; i += 256) {
+                    const unsigned long long key = pass[i];
+                    if (key < bound && key > best) best = key;
+                }
+                best = wave_max(best);
+                if (lane == 0) s_red[wave] = best;
+                __syncthreads();
+                best = s_red[0];
+                for (int w = 1; w < 4; ++w) best = s_red[w] > best ? s_red[w] : best;
+                if (tid == 0) s_sel[r] = best;
+                bound = best;
+                __syncthreads();
+            }
+        }
+        __syncthreads();
+
+        // 4. where hub columns were skipped, the exact saving by list intersection: a candidate per wave,
+        //    the shorter list searched in the longer
+        if (nhub > 0) {
+            for (unsigned s = wave; s < nsel; s += 4) {
+                const int32_t y = key_row(s_sel[s]);
+                const int64_t yb = a.rowptr[y], ny = a.rowptr[y + 1] - yb;
+                const int32_t* sh = a.colidx + xb;
+                const int32_t* lg = a.colidx + yb;
+                int64_t nsh = nx, nlg = ny;
+                if (nlg < nsh) {
+                    const int32_t* t = sh;
+                    sh = lg;
+                    lg = t;
+                    nsh = ny;
+                    nlg = nx;
+                }
+                int64_t found = 0;
+                for (int64_t i = lane; i < nsh; i += 64) {
+                    const int32_t v = sh[i];
+                    int64_t lo = 0, hi = nlg;
+                    while (lo < hi) {
+                        const int64_t mid = (lo + hi) >> 1;
+                        if (lg[mid] < v)
+                            lo = mid + 1;
+                        else
+                            hi = mid;
+                    }
+                    found += (lo < nlg && lg[lo] == v);
+                }
+                found = wave_sum(found);
+                if (lane == 0) s_saving[s] = 2 * found - ny;
+            }
+        } else {
+            for (unsigned s = tid; s < nsel; s += 256) s_saving[s] = (long long)(s_sel[s] >> 32);
+        }
+        __syncthreads();
+
+        // 5. the best `keep` by exact saving (ties: smaller row index)
+        if (tid == 0) {
+            unsigned long long fin[kSelMax];
+            int nf = 0;
+            for (unsigned s = 0; s < nsel; ++s)
+                if (s_saving[s] >= a.min_saving) fin[nf++] = make_key(s_saving[s], key_row(s_sel[s]));
+            for (int i = 1; i < nf; ++i) {  // insertion sort, descending
+                const unsigned long long key = fin[i];
+                int j = i - 1;
+                while (j >= 0 && fin[j] < key) {
+                    fin[j + 1] = fin[j];
+                    --j;
+                }
+                fin[j + 1] = key;
+            }
+            const int nout = nf < a.keep ? nf : a.keep;
+            for (int i = 0; i < nout; ++i) {
+                a.out_y[(int64_t)x * a.keep + i] = key_row(fin[i]);
+                a.out_w[(int64_t)x * a.keep + i] = (int32_t)(nx - (int64_t)(fin[i] >> 32));
+            }
+            a.out_n[x] = nout;
+        }
+    }
+}
+
+struct DeviceBuffers {
+    std::vector<void*> ptrs;
+    ~DeviceBuffers() {
+        for (void* p : ptrs) hipFree(p);
+    }
+    template <typename T>
+    hipError_t alloc(T** out, size_t count) {
+        *out = nullptr;
+        hipError_t e = hipMalloc((void**)out, std::max<size_t>(count, 1) * sizeof(T));
+        if (e == hipSuccess) ptrs.push_back(*out);
+        return e;
+    }
+};
+
+#define CAND_TRY(call, status)                                     \
+    do {                                                          \
+        hipError_t err_ = (call);                                 \
+        if (err_ != hipSuccess) {                                 \
+            cbm_set_error_detail(#call, hipGetErrorString(err_)); \
+            if (cur != dev) hipSetDevice(cur);                    \
+            return (status);                                      \
+        }                                                         \
+    } while (0)
+
+}  // namespace
+
+cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t* rowptr, const int32_t* colidx,
+                                 const int64_t* tptr, const int32_t* trow, int64_t hub_cap, int64_t min_saving,
+                                 int32_t keep, std::vector<int32_t>* out_n, std::vector<int32_t>* out_y,
+                                 std::vector<int32_t>* out_w) {
+    if (keep < 1 || keep > kCandMax) return CBM_ERR_INVALID_ARG;
+    out_n->assign(m, 0);
+    out_y->assign((size_t)m * keep, 0);
+    out_w->assign((size_t)m * keep, 0);
+    if (m == 0) return CBM_OK;
+    int cur = -1, dev = device;
+    {
+        hipError_t e = hipGetDevice(&cur);
+        if (e != hipSuccess) {
+            cbm_set_error_detail("hipGetDevice", hipGetErrorString(e));
+            return CBM_ERR_HIP;
+        }
+    }
+    if (dev < 0) dev = cur;
+    if (cur != dev) CAND_TRY(hipSetDevice(dev), CBM_ERR_HIP);
+    const int64_t nnz = rowptr[m];
+
+    // heaviest rows first: the expansion of row x touches sum over its non-hub columns of the column's rows
+    std::vector<int32_t> order(m);
+    {
+        std::vector<std::pair<int64_t, int32_t>> heavy;
+        std::vector<int32_t> rest;
+        rest.reserve(m);
+        for (int64_t x = 0; x < m; ++x) {
+            int64_t work = 0;
+            for (int64_t p = rowptr[x]; p < rowptr[x + 1]; ++p) {
+                const int64_t deg = tptr[colidx[p] + 1] - tptr[colidx[p]];
+                if (hub_cap < 0 || deg <= hub_cap) work += deg;
+            }
+            if (work >= (1 << 18))
+                heavy.push_back({work, (int32_t)x});
+            else
+                rest.push_back((int32_t)x);
+        }
+        std::sort(heavy.begin(), heavy.end(), [](const auto& p, const auto& q) { return p.first > q.first; });
+        size_t w = 0;
+        for (auto& p : heavy) order[w++] = p.second;
+        for (int32_t x : rest) order[w++] = x;
+    }
+
+    // one counter array, one touched list and one key list of m entries per workgroup
+    size_t free_b = 0, total_b = 0;
+    CAND_TRY(hipMemGetInfo(&free_b, &total_b), CBM_ERR_HIP);
+    const size_t fixed = (size_t)(m + 1) * 8 + (size_t)nnz * 4 + (size_t)(n + 1) * 8 + (size_t)nnz * 4 + (size_t)m * 4 +
+                         (size_t)m * 4 * (1 + 2 * (size_t)keep);
+    const size_t per_wg = (size_t)m * 16;
+    const size_t budget = std::min<size_t>((size_t)24 << 30, free_b / 2 > fixed ? free_b / 2 - fixed : 0);
+    int64_t nwg = (int64_t)std::min<size_t>(1024, budget / per_wg);
+    nwg = std::min<int64_t>(nwg, m);
+    if (nwg < 1) {
+        cbm_set_error_detail("cbm_device_candidates", "not enough device memory for one workgroup's counters");
+        if (cur != dev) hipSetDevice(cur);
+        return CBM_ERR_ALLOC;
+    }
+
+    DeviceBuffers buf;
+    CandArgs a{};
+    int64_t *d_rowptr, *d_tptr;
+    int32_t *d_colidx, *d_trow, *d_order;
+    CAND_TRY(buf.alloc(&d_rowptr, m + 1), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&d_colidx, nnz), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&d_tptr, n + 1), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&d_trow, nnz), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&d_order, m), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&a.next, 1), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&a.cnt, (size_t)nwg * m), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&a.touched, (size_t)nwg * m), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&a.pass, (size_t)nwg * m), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&a.out_n, m), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&a.out_y, (size_t)m * keep), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&a.out_w, (size_t)m * keep), CBM_ERR_ALLOC);
+    CAND_TRY(hipMemcpy(d_rowptr, rowptr, (size_t)(m + 1) * 8, hipMemcpyHostToDevice), CBM_ERR_HIP);
+    if (nnz > 0) {
+        CAND_TRY(hipMemcpy(d_colidx, colidx, (size_t)nnz * 4, hipMemcpyHostToDevice), CBM_ERR_HIP);
+        CAND_TRY(hipMemcpy(d_trow, trow, (size_t)nnz * 4, hipMemcpyHostToDevice), CBM_ERR_HIP);
+    }
+    CAND_TRY(hipMemcpy(d_tptr, tptr, (size_t)(n + 1) * 8, hipMemcpyHostToDevice), CBM_ERR_HIP);
+    CAND_TRY(hipMemcpy(d_order, order.data(), (size_t)m * 4, hipMemcpyHostToDevice), CBM_ERR_HIP);
+    CAND_TRY(hipMemset(a.next, 0, sizeof(unsigned long long)), CBM_ERR_HIP);
+    CAND_TRY(hipMemset(a.cnt, 0, (size_t)nwg * m * sizeof(uint32_t)), CBM_ERR_HIP);
+    a.m = m;
+    a.rowptr = d_rowptr;
+    a.colidx = d_colidx;
+    a.tptr = d_tptr;
+    a.trow = d_trow;
+    a.order = d_order;
+    a.hub_cap = hub_cap;
+    a.min_saving = min_saving;
+    a.keep = keep;
+    hipLaunchKernelGGL(cbm_candidates_kernel, dim3((unsigned)nwg), dim3(256), 0, 0, a);
+    CAND_TRY(hipGetLastError(), CBM_ERR_HIP);
+    CAND_TRY(hipDeviceSynchronize(), CBM_ERR_HIP);
+    CAND_TRY(hipMemcpy(out_n->data(), a.out_n, (size_t)m * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
+    CAND_TRY(hipMemcpy(out_y->data(), a.out_y, (size_t)m * keep * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
+    CAND_TRY(hipMemcpy(out_w->data(), a.out_w, (size_t)m * keep * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
+    if (cur != dev) hipSetDevice(cur);
+    return CBM_OK;
+}

@@ -138,7 +138,8 @@ struct Builder {
     void self_loops(const int64_t* in_rowptr, const int32_t* in_colidx);
     std::vector<int64_t> optr;  // candidate edges bucketed by parent
     std::vector<int32_t> ochild, ow;
-    void find_candidates();
+    bool device_candidates = false;  // run the candidate search on the GPU
+    cbm_status find_candidates();
     void prim(int64_t seeds);
     void arborescence();
     void all_roots();
@@ -209,7 +210,7 @@ void Builder::all_roots() {
 }
 
 // Candidate parents: for every row, the rows that share columns with it, ranked by exact Hamming distance.
-void Builder::find_candidates() {
+cbm_status Builder::find_candidates() {
     // transpose: rows holding each column
     std::vector<int64_t> tptr(n + 1, 0);
     std::vector<int32_t> trow(nnz);
@@ -224,7 +225,15 @@ void Builder::find_candidates() {
 
     // candidate parents: rows sharing columns, ranked by exact Hamming distance
     std::vector<std::vector<Cand>> cand_per_thread(nthreads);
-    {
+    if (device_candidates) {
+        std::vector<int32_t> cn, cy, cw;
+        const cbm_status st = cbm_device_candidates(h->opts.device, m, n, rowptr, colidx, tptr.data(), trow.data(), hub_cap,
+                                                    min_saving, max_cand, &cn, &cy, &cw);
+        if (st != CBM_OK) return st;
+        auto& out = cand_per_thread[0];
+        for (int64_t x = 0; x < m; ++x)
+            for (int32_t i = 0; i < cn[x]; ++i) out.push_back({(int32_t)x, cy[x * max_cand + i], cw[x * max_cand + i]});
+    } else {
         std::vector<std::vector<int32_t>> counters(nthreads), touched(nthreads);
         parallel_chunks(nthreads, m, 64, [&](int64_t b, int64_t e, int tid) {
             auto& cnt = counters[tid];
@@ -313,6 +322,7 @@ void Builder::find_candidates() {
             std::vector<Cand>().swap(v);
         }
     }
+    return CBM_OK;
 }
 
 // Prim growth from the virtual vertex over the candidate edges, depth-capped.  `seeds` rows, evenly
@@ -892,8 +902,12 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     if (std::getenv("CBM_SPLIT_MIN")) split_choices = {B.split_min};
     bool tree = B.max_depth != 1 && m > 1;
     const bool exact_tree = (o.flags & CBM_FLAG_EXACT_TREE) != 0;
+    if (o.flags & CBM_FLAG_DEVICE_BUILD) {
+        if ((o.flags & CBM_FLAG_HOST_ONLY) || B.max_cand < 1 || B.max_cand > 16) return CBM_ERR_INVALID_ARG;
+        B.device_candidates = true;
+    }
     if (tree && exact_tree) {
-        B.find_candidates();
+        if ((st = B.find_candidates()) != CBM_OK) return st;
         B.arborescence();
         B.tree_index();
         double best_us = 1e300;
@@ -907,7 +921,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
         }
         B.lap("exact arborescence");
     } else if (tree) {
-        B.find_candidates();
+        if ((st = B.find_candidates()) != CBM_OK) return st;
         const int64_t forced_len = env_or("CBM_PATH_MAX", 0);
         const int64_t forced_seeds = o.seed_roots > 0 ? o.seed_roots : o.seed_roots < 0 ? 0 : env_or("CBM_SEED_ROOTS", -1);
         double best_us = 1e300;

@@ -97,6 +97,12 @@ cbm_status cbm_decompress_host(const cbm_handle* h, int64_t* rowptr, int32_t* co
 enum CbmEpilogue { CBM_EPI_NONE = 0, CBM_EPI_ROWSCALE = 1, CBM_EPI_ROWSCALE_RELU = 2, CBM_EPI_MEAN = 3, CBM_EPI_SELF = 4 };
 cbm_status cbm_upload(cbm_handle* h);
 void cbm_release_device(cbm_handle* h);
+// Candidate search of the builder on the GPU (same candidate set as the host search): for every row the
+// best `keep` (<= 16) rows to compress it against, out_y / out_w = parent and distance, out_n = how many.
+cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t* rowptr, const int32_t* colidx,
+                                 const int64_t* tptr, const int32_t* trow, int64_t hub_cap, int64_t min_saving,
+                                 int32_t keep, std::vector<int32_t>* out_n, std::vector<int32_t>* out_y,
+                                 std::vector<int32_t>* out_w);
 cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
                               CbmEpilogue epi, float self_weight, void* stream);
 // dense fp32 MFMA matmul (cbm_gemm.hip)
