@@ -233,7 +233,7 @@ def report(args, torch, cbm, wl, orc, csr_ref):
              "alg. GB/s = algorithmic bytes / time (can pass the 8 TB/s HBM peak when gathers hit in L2 / Infinity Cache). "
              "GPU CSR = the same kernels on a handle with every row stored in full. CPU columns: OpenMP CSR SpMM on all "
              "host cores (fp32) and the numpy oracle on a row sample (1 thread).", "",
-             "| graph | n | nnz(A v I) | k | deltas/nnz | depth / rounds | build s | CBM ms | alg. GB/s | frac of HBM peak | "
+             "| graph | n | nnz(A v I) | k | deltas/nnz | depth / rounds | build s (candidate search on the host) | CBM ms | alg. GB/s | frac of HBM peak | "
              "edges*k/s | GPU CSR ms | CBM speedup | CPU OMP CSR ms | oracle GB/s | parity err |",
              "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
     gcn_lines = ["", "| graph | GCN shape | CBM ms | as HIP graph replay ms | with CSR handle ms | speedup | "
@@ -247,8 +247,12 @@ def report(args, torch, cbm, wl, orc, csr_ref):
         g = wl.make_graph(name, **({"scale": args.rmat_scale} if name == "rmat" else {}))
         log(f"graph {name}: n={g.n} nnz={g.nnz} ({time.perf_counter() - t0:.1f} s)")
         t0 = time.perf_counter()
-        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=d["alpha"], max_depth=args.max_depth)
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=d["alpha"], max_depth=args.max_depth,
+                          device_build=not args.host_build)
         tb = time.perf_counter() - t0
+        t0 = time.perf_counter()   # the same build with the candidate search on the host threads, for the table only
+        cbm.cbm_free(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=d["alpha"], max_depth=args.max_depth))
+        tb_host = time.perf_counter() - t0
         hc = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=1)
         for k in ks:
             Xh = wl.gaussian_features(g.n, k, g.meta["seed"])
@@ -257,7 +261,7 @@ def report(args, torch, cbm, wl, orc, csr_ref):
             ob = cpu_oracle_baseline(orc, g, Xh, k, budget_s=5.0)
             st = r["stats"]
             nd = st["num_delta_plus"] + st["num_delta_minus"]
-            lines.append(f"| {name} | {g.n} | {st['nnz']} | {k} | {nd / st['nnz']:.3f} | {st['depth']} / {st['rounds']} | {tb:.2f} | "
+            lines.append(f"| {name} | {g.n} | {st['nnz']} | {k} | {nd / st['nnz']:.3f} | {st['depth']} / {st['rounds']} | {tb:.2f} ({tb_host:.2f}) | "
                          f"{r['ms']:.4f} | {r['value']:.0f} | {r['value'] / HBM_PEAK_GBS:.3f} | {r['edges_k_per_s']:.3e} | "
                          f"{r['gpu_csr']['ms']:.4f} | {r['speedup']:.2f}x | {cpu['ms']:.2f} ({cpu['threads']} thr) | "
                          f"{ob['value']:.2f} | {r['parity_err']:.1e} |")
@@ -284,7 +288,8 @@ def report(args, torch, cbm, wl, orc, csr_ref):
                              f"{'n/a (graph too large for the whole-graph oracle)' if e is None else format(e, '.1e')} |")
             results.append(dict(workload=name, gcn=gc))
         if name == "collaboration":  # the iterated product X_{t+1} = A X_t of the collaboration config
-            hp = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=d["alpha"], max_depth=args.max_depth)
+            hp = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=d["alpha"], max_depth=args.max_depth,
+                               device_build=not args.host_build)
             a = torch.from_numpy(wl.gaussian_features(g.n, 128, 5)).cuda()
             b = torch.empty_like(a)
 
@@ -330,7 +335,8 @@ def alpha_sweep(args, torch, cbm, wl):
         ms_csr = time_steps(torch, lambda: cbm.cbm_spmm_normalized(hc, X, Y), args.steps, args.warmup)
         cbm.cbm_free(hc)
         for alpha in (0, 1, 2, 4, 8, 16, 32, 64):
-            h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha, max_depth=16)
+            h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha, max_depth=16,
+                              device_build=not args.host_build)
             st = cbm.cbm_stats(h)
             ms = time_steps(torch, lambda: cbm.cbm_spmm_normalized(h, X, Y), args.steps, args.warmup)
             nd = st["num_delta_plus"] + st["num_delta_minus"]
@@ -353,6 +359,7 @@ def main():
     ap.add_argument("--alpha", type=int, default=-1)
     ap.add_argument("--max-depth", type=int, default=0)
     ap.add_argument("--rmat-scale", type=int, default=21)
+    ap.add_argument("--host-build", action="store_true", help="run the builder's candidate search on the host threads, not on the GPU")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baselines")
     ap.add_argument("--no-gcn", action="store_true", help="skip the GCN inference timing")
     ap.add_argument("--no-csr", action="store_true", help="skip the all-roots (GPU CSR) comparison")
@@ -409,7 +416,8 @@ def main():
     log(f"graph {g.name}: n={g.n} nnz={g.nnz} max_deg={g.meta['max_degree']} ({time.perf_counter() - t0:.1f} s)")
     Xh = wl.gaussian_features(g.n, k, g.meta["seed"])
     t0 = time.perf_counter()
-    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha, max_depth=args.max_depth)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha, max_depth=args.max_depth,
+                      device_build=not args.host_build)
     st = cbm.cbm_stats(h)
     log(f"cbm_build: {time.perf_counter() - t0:.1f} s, deltas={st['num_delta_plus'] + st['num_delta_minus']} "
         f"of nnz={st['nnz']}, roots={st['num_roots']}, depth={st['depth']}, rounds={st['rounds']}")
@@ -430,7 +438,8 @@ def main():
         else:  # the timed graph has no GCN in its configuration: use the citation-like one (PubMed's shape)
             gc = wl.make_graph("citation")
             dc = DEFAULTS["citation"]
-            h2 = cbm.cbm_build(gc.n, gc.n, gc.rowptr, gc.colidx, add_self_loops=True, alpha=dc["alpha"])
+            h2 = cbm.cbm_build(gc.n, gc.n, gc.rowptr, gc.colidx, add_self_loops=True, alpha=dc["alpha"],
+                               device_build=not args.host_build)
             h2c = cbm.cbm_build(gc.n, gc.n, gc.rowptr, gc.colidx, add_self_loops=True, max_depth=1)
             gcn = bench_gcn(torch, cbm, wl, orc, gc, h2, h2c, dc["gcn"], args.steps, args.warmup)
         log(f"GCN ({gcn['workload']}): {gcn['ms']:.4f} ms (CSR handle {gcn['ms_with_csr_handle']} ms)")

@@ -11,7 +11,10 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cstdio>
+#include <cstdlib>
+#include <thread>
 #include <vector>
 
 #include "cbm_internal.h"
@@ -104,9 +107,16 @@ __global__ __launch_bounds__(256) void cbm_candidates_kernel(const CandArgs a) {
                 if (gl == 0) ++myhub;
                 continue;
             }
-            for (int64_t q = gl; q < deg; q += 16) {
-                const int32_t y = a.trow[tb + q];
-                if (atomicAdd(&cnt[y], 1u) == 0u) touched[atomicAdd(&s_ntouched, 1u)] = y;
+            for (int64_t q = gl; q < deg; q += 64) {  // four counters in flight per lane
+                int32_t y[4];
+                uint32_t old[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) y[u] = q + 16 * u < deg ? a.trow[tb + q + 16 * u] : -1;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) old[u] = y[u] >= 0 ? atomicAdd(&cnt[y[u]], 1u) : 1u;
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (old[u] == 0u) touched[atomicAdd(&s_ntouched, 1u)] = y[u];
             }
         }
         if (myhub) atomicAdd(&s_nhub, myhub);
@@ -266,30 +276,44 @@ cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t
     if (dev < 0) dev = cur;
     if (cur != dev) CAND_TRY(hipSetDevice(dev), CBM_ERR_HIP);
     const int64_t nnz = rowptr[m];
+    const bool verbose = std::getenv("CBM_VERBOSE") != nullptr;
+    auto last = std::chrono::steady_clock::now();
+    auto lap = [&](const char* what) {
+        const auto now = std::chrono::steady_clock::now();
+        if (verbose)
+            std::fprintf(stderr, "[cbm_build]   device candidates: %-18s %.3f s\n", what,
+                         std::chrono::duration<double>(now - last).count());
+        last = now;
+    };
 
     // heaviest rows first: the expansion of row x touches sum over its non-hub columns of the column's rows
     std::vector<int32_t> order(m);
     {
+        std::vector<int64_t> work(m);
+        const int nt = (int)std::max(1u, std::min(32u, std::thread::hardware_concurrency()));
+        std::vector<std::thread> pool;
+        for (int t = 0; t < nt; ++t)
+            pool.emplace_back([&, t] {
+                for (int64_t x = m * t / nt; x < m * (t + 1) / nt; ++x) {
+                    int64_t w = 0;
+                    for (int64_t p = rowptr[x]; p < rowptr[x + 1]; ++p) {
+                        const int64_t deg = tptr[colidx[p] + 1] - tptr[colidx[p]];
+                        if (hub_cap < 0 || deg <= hub_cap) w += deg;
+                    }
+                    work[x] = w;
+                }
+            });
+        for (auto& th : pool) th.join();
         std::vector<std::pair<int64_t, int32_t>> heavy;
-        std::vector<int32_t> rest;
-        rest.reserve(m);
-        for (int64_t x = 0; x < m; ++x) {
-            int64_t work = 0;
-            for (int64_t p = rowptr[x]; p < rowptr[x + 1]; ++p) {
-                const int64_t deg = tptr[colidx[p] + 1] - tptr[colidx[p]];
-                if (hub_cap < 0 || deg <= hub_cap) work += deg;
-            }
-            if (work >= (1 << 18))
-                heavy.push_back({work, (int32_t)x});
-            else
-                rest.push_back((int32_t)x);
-        }
-        std::sort(heavy.begin(), heavy.end(), [](const auto& p, const auto& q) { return p.first > q.first; });
         size_t w = 0;
+        for (int64_t x = 0; x < m; ++x)
+            if (work[x] >= (1 << 18)) heavy.push_back({work[x], (int32_t)x});
+        std::sort(heavy.begin(), heavy.end(), [](const auto& p, const auto& q) { return p.first > q.first; });
         for (auto& p : heavy) order[w++] = p.second;
-        for (int32_t x : rest) order[w++] = x;
+        for (int64_t x = 0; x < m; ++x)
+            if (work[x] < (1 << 18)) order[w++] = (int32_t)x;
     }
-
+    lap("row order");
     // one counter array, one touched list and one key list of m entries per workgroup
     size_t free_b = 0, total_b = 0;
     CAND_TRY(hipMemGetInfo(&free_b, &total_b), CBM_ERR_HIP);
@@ -330,6 +354,8 @@ cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t
     CAND_TRY(hipMemcpy(d_order, order.data(), (size_t)m * 4, hipMemcpyHostToDevice), CBM_ERR_HIP);
     CAND_TRY(hipMemset(a.next, 0, sizeof(unsigned long long)), CBM_ERR_HIP);
     CAND_TRY(hipMemset(a.cnt, 0, (size_t)nwg * m * sizeof(uint32_t)), CBM_ERR_HIP);
+    CAND_TRY(hipDeviceSynchronize(), CBM_ERR_HIP);
+    lap("alloc + upload");
     a.m = m;
     a.rowptr = d_rowptr;
     a.colidx = d_colidx;
@@ -342,9 +368,11 @@ cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t
     hipLaunchKernelGGL(cbm_candidates_kernel, dim3((unsigned)nwg), dim3(256), 0, 0, a);
     CAND_TRY(hipGetLastError(), CBM_ERR_HIP);
     CAND_TRY(hipDeviceSynchronize(), CBM_ERR_HIP);
+    lap("kernel");
     CAND_TRY(hipMemcpy(out_n->data(), a.out_n, (size_t)m * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
     CAND_TRY(hipMemcpy(out_y->data(), a.out_y, (size_t)m * keep * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
     CAND_TRY(hipMemcpy(out_w->data(), a.out_w, (size_t)m * keep * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
+    lap("download");
     if (cur != dev) hipSetDevice(cur);
     return CBM_OK;
 }
