@@ -7,6 +7,11 @@
 #include <vector>
 #include "cbm_internal.h"
 void cbm_set_error_detail(const char*, const char*) {}
+// the GPU candidate search is not part of a host-only build
+cbm_status cbm_device_candidates(int, int64_t, int64_t, const int64_t*, const int32_t*, const int64_t*, const int32_t*, int64_t,
+                                 int64_t, int32_t, std::vector<int32_t>*, std::vector<int32_t>*, std::vector<int32_t>*) {
+    return CBM_ERR_STATE;
+}
 const char* cbm_get_error_detail() { return ""; }
 int main() {
     std::mt19937 rng(1);
