@@ -161,9 +161,11 @@ def bench_product(torch, cbm, orc, g, h, hc, Xh, k, steps, warmup, workload, alp
                     frac=achieved / HBM_PEAK_GBS, traffic=traffic, avg_launch_ms=avg_ms,
                     launches_per_step=lv["launches"] / nprof, algorithmic_bytes_per_launch=avg_bytes,
                     ms_per_step_profiled=ms_prof,
+                    traffic_gbs=(traffic / avg_ms / 1e6 if traffic and avg_ms > 0 else None),
+                    traffic_frac_of_peak=(traffic / avg_ms / 1e6 / HBM_PEAK_GBS if traffic and avg_ms > 0 else None),
                     note="algorithmic bytes exceed HBM traffic where gathered rows of X hit in L2 / Infinity Cache, "
                          "so frac can pass 1; traffic = rocprofv3 FETCH_SIZE+WRITE_SIZE per launch (L2-miss bytes)",
-                    other_kernels_ms_per_step={{2: "combine", 3: "rowscale"}.get(kk, str(kk)): v["ms"] / nprof
+                    other_kernels_ms_per_step={{2: "combine", 3: "finish"}.get(kk, str(kk)): v["ms"] / nprof
                                                for kk, v in agg.items() if kk not in (0, 1)})
 
     step()
