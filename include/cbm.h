@@ -52,6 +52,13 @@ typedef enum {
                                     1 <= max_candidates <= 16 (the default qualifies); not with
                                     CBM_FLAG_HOST_ONLY.                                         */
 
+#define CBM_FLAG_TRANSPOSE 8u /* compress the transpose: the handle holds A^T (n x m; (A v I)^T with
+                                 add_self_loops) and every product and query works on that matrix.
+                                 The normalised product keeps D = the row sums of A v I as given, so
+                                 it computes (D^-1/2 (A + I) D^-1/2)^T X: the backward pass of the
+                                 normalised product for a directed graph (for a symmetric one the
+                                 transpose is the matrix itself and this flag changes nothing).   */
+
 /*
  * Build options.  A NULL pointer means all zeros, i.e. the defaults below.
  *

@@ -136,6 +136,7 @@ struct Builder {
 
     cbm_status validate(const int64_t* in_rowptr, const int32_t* in_colidx);
     void self_loops(const int64_t* in_rowptr, const int32_t* in_colidx);
+    void transpose_matrix();
     std::vector<int64_t> optr;  // candidate edges bucketed by parent
     std::vector<int32_t> ochild, ow;
     bool device_candidates = false;  // run the candidate search on the GPU
@@ -200,6 +201,25 @@ void Builder::self_loops(const int64_t* in_rowptr, const int32_t* in_colidx) {
     });
     rowptr = own_rowptr.data();
     colidx = own_colidx.data();
+}
+
+// Replace the matrix by its transpose (n x m).  Rows are scanned in order, so every new row comes out sorted.
+void Builder::transpose_matrix() {
+    std::vector<int64_t> tp(n + 1, 0);
+    const int64_t nz = rowptr[m];
+    for (int64_t p = 0; p < nz; ++p) ++tp[colidx[p] + 1];
+    for (int64_t j = 0; j < n; ++j) tp[j + 1] += tp[j];
+    std::vector<int32_t> tc(nz);
+    {
+        std::vector<int64_t> fill(tp.begin(), tp.end() - 1);
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) tc[fill[colidx[p]]++] = (int32_t)i;
+    }
+    own_rowptr.swap(tp);
+    own_colidx.swap(tc);
+    rowptr = own_rowptr.data();
+    colidx = own_colidx.data();
+    std::swap(m, n);
 }
 
 void Builder::all_roots() {
@@ -874,16 +894,23 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     if (o.add_self_loops) B.self_loops(in_rowptr, in_colidx);
     B.nnz = B.rowptr[m];
     if (B.nnz >= (int64_t)UINT32_MAX) return CBM_ERR_UNSUPPORTED;
+    if (h->square_self_loops) {  // D^-1/2 of A v I: D is the row sums of the matrix as given, transposed or not
+        h->dinv.resize(m);
+        for (int64_t i = 0; i < m; ++i) h->dinv[i] = (float)(1.0 / std::sqrt((double)(B.rowptr[i + 1] - B.rowptr[i])));
+    }
+    if (o.flags & CBM_FLAG_TRANSPOSE) {
+        B.transpose_matrix();
+        m = B.m;
+        n = B.n;
+        h->m = m;
+        h->n = n;
+    }
     h->rownnz.resize(m);
     for (int64_t i = 0; i < m; ++i) h->rownnz[i] = (int32_t)(B.rowptr[i + 1] - B.rowptr[i]);
     B.lap("validate + A v I");
 
     h->rinv.resize(m);  // 1/nnz per row: the mean aggregator's row weight
     for (int64_t i = 0; i < m; ++i) h->rinv[i] = B.rlen(i) > 0 ? (float)(1.0 / (double)B.rlen(i)) : 0.0f;
-    if (h->square_self_loops) {  // D^-1/2 of A v I
-        h->dinv.resize(m);
-        for (int64_t i = 0; i < m; ++i) h->dinv[i] = (float)(1.0 / std::sqrt((double)B.rlen(i)));
-    }
 
     // ---- tree, paths, rounds ---------------------------------------------------------------------
     // The tree is cut into vertical paths.  A path is ONE work item: its running sum stays in

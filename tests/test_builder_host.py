@@ -243,3 +243,26 @@ def test_invariants_on_reduced_workloads(name, kw):
     t = cbm.cbm_get_tree(h)
     comp = t["parent"] >= 0
     assert np.all(t["level"][comp] == t["level"][t["parent"][comp]] + 1)
+
+
+@pytest.mark.parametrize("self_loops", [False, True])
+def test_transposed_build_holds_the_transpose(self_loops):
+    """CBM_FLAG_TRANSPOSE: the handle is the CBM of A^T (of (A v I)^T with self loops) and satisfies the same
+    invariants; the transpose is checked against scipy's."""
+    import scipy.sparse as sp
+
+    rng = np.random.default_rng(21 + self_loops)
+    m, n = (70, 70) if self_loops else (50, 90)
+    rows = _random_rows(rng, m, n, 0.15)                 # directed: not symmetric
+    rows[3] = []
+    rowptr, colidx = _csr(rows)
+    h = cbm.cbm_build(m, n, rowptr, colidx, alpha=1, add_self_loops=self_loops, transpose=True, host_only=True, max_depth=16)
+    A = sp.csr_matrix((np.ones(len(colidx)), colidx, rowptr), shape=(m, n))
+    if self_loops:
+        A = ((A + sp.identity(m, format="csr")) > 0).astype(np.float64)
+    At = sp.csr_matrix(A.T)
+    At.sort_indices()
+    s = cbm.cbm_stats(h)
+    assert (s["m"], s["n"], s["nnz"]) == (n, m, At.nnz)
+    _check_invariants(n, m, At.indptr.astype(np.int64), At.indices.astype(np.int32), h, 1, False)
+    cbm.cbm_free(h)

@@ -227,6 +227,38 @@ def test_mean_and_gin_on_split_and_empty_rows(env):
     assert e.value.status == 6
 
 
+def test_transposed_handle_is_the_adjoint(env):
+    """A directed graph: the handle built with transpose=True computes A^T.G (and A_hat^T.G), the backward pass of
+    the product.  Checked against the dense definition and through <Y, A X> = <A^T Y, X> on integers, exactly."""
+    torch, cbm = env
+    rng = np.random.default_rng(17)
+    n, k = 900, 24
+    rows = [sorted(rng.choice(n, size=int(s), replace=False).tolist()) for s in rng.integers(0, 60, size=n)]
+    rows[0] = sorted(rng.choice(n, size=700, replace=False).tolist())          # a split row, and a hub column below
+    rows = [sorted(set(r) | ({5} if i % 3 else set())) for i, r in enumerate(rows)]
+    rowptr, colidx = _csr(rows)
+    A = orc.dense_from_csr(n, n, rowptr, colidx)
+    h = cbm.cbm_build(n, n, rowptr, colidx, max_depth=16)
+    ht = cbm.cbm_build(n, n, rowptr, colidx, max_depth=16, transpose=True)
+    X, G = wl.integer_features(n, k, 1), wl.integer_features(n, k, 2)
+    Y = _run(env, "cbm_spmm", h, X, n).astype(np.float64)
+    Z = _run(env, "cbm_spmm", ht, G, n).astype(np.float64)
+    assert np.array_equal(Z, A.T @ G.astype(np.float64))
+    assert (Y * G).sum() == (Z * X).sum()                                       # the adjoint identity, in integers
+    # normalised: D stays the row sums of A v I as given
+    hn = cbm.cbm_build(n, n, rowptr, colidx, max_depth=16, add_self_loops=True, transpose=True)
+    Gg = wl.gaussian_features(n, k, 3)
+    ref = orc.normalized_dense(A).T @ Gg.astype(np.float64)
+    assert row_scaled_error(_run(env, "cbm_spmm_normalized", hn, Gg, n), ref) <= TOL
+    # rectangular: (m x n)^T is n x m
+    m2, n2 = 300, 500
+    rowptr, colidx = _csr([sorted(rng.choice(n2, size=int(s), replace=False).tolist()) for s in rng.integers(0, 40, size=m2)])
+    hr = cbm.cbm_build(m2, n2, rowptr, colidx, max_depth=16, transpose=True)
+    G2 = wl.integer_features(m2, 8, 4)
+    got = _run(env, "cbm_spmm", hr, G2, n2).astype(np.float64)
+    assert np.array_equal(got, orc.dense_from_csr(m2, n2, rowptr, colidx).T @ G2.astype(np.float64))
+
+
 def test_degenerate_shapes(env):
     torch, cbm = env
     # empty matrix
