@@ -55,6 +55,25 @@ def time_steps(torch, fn, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / max(1, steps)
 
 
+def per_step_ms(torch, fn, steps):
+    """Duration of each of `steps` calls from events recorded between them on the current stream."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    ev[0].record()
+    for i in range(steps):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    return [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+
+
+def device_copy_gbs(torch, nbytes=1 << 30, reps=5):
+    """Read + write rate of a plain device-to-device copy on this machine."""
+    src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").fill_(1.0)
+    dst = torch.empty_like(src)
+    ms = time_steps(torch, lambda: dst.copy_(src), reps, 2)
+    return 2 * nbytes / ms / 1e6
+
+
 def algorithmic_bytes(stats, k, normalized):
     """Bytes the method itself must move in one product: per delta one X row + its 4-byte entry
     (+ one d^-1/2 value when normalised); per row one Y write + its 4-byte marker entry (+ d^-1/2);
@@ -137,6 +156,7 @@ def bench_product(torch, cbm, orc, g, h, hc, Xh, k, steps, warmup, workload, alp
     Y = torch.empty((g.n, k), device="cuda")
     step = lambda: cbm.cbm_spmm_normalized(h, X, Y)  # noqa: E731
     ms = time_steps(torch, step, steps, warmup)
+    ms_median = float(np.median(per_step_ms(torch, step, steps)))
     b_alg = algorithmic_bytes(st, k, True)
     log(f"{workload} k={k}: cbm_spmm_normalized {ms:.4f} ms/step, {b_alg / ms / 1e6:.1f} GB/s algorithmic")
 
@@ -183,7 +203,10 @@ def bench_product(torch, cbm, orc, g, h, hc, Xh, k, steps, warmup, workload, alp
                        edges_k_per_s=sc["nnz"] * k / ms_csr * 1e3, kind="same kernels, all rows stored in full")
         log(f"{workload} k={k}: GPU CSR (all-roots handle) {ms_csr:.4f} ms/step; CBM speedup {ms_csr / ms:.3f}x")
     nd = st["num_delta_plus"] + st["num_delta_minus"]
-    return dict(ms=ms, value=b_alg / ms / 1e6, b_alg=b_alg, roofline=roofline, parity_err=err, rows_checked=len(rows),
+    copy_gbs = device_copy_gbs(torch)
+    roofline["device_copy_gbs"] = copy_gbs
+    roofline["traffic_frac_of_device_copy"] = (roofline["traffic_gbs"] / copy_gbs) if roofline["traffic_gbs"] else None
+    return dict(ms=ms, ms_median=ms_median, value=b_alg / ms / 1e6, b_alg=b_alg, roofline=roofline, parity_err=err, rows_checked=len(rows),
                 gpu_csr=gpu_csr, speedup=None if ms_csr is None else ms_csr / ms,
                 edges_k_per_s=st["nnz"] * k / ms * 1e3, deltas_k_per_s=nd * k / ms * 1e3, stats=st)
 
@@ -455,6 +478,7 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": r["ms"],
+        "ms_per_step_median": r["ms_median"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
