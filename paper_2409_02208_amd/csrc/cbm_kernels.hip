@@ -1,13 +1,15 @@
 // CBM product kernels for gfx950 (wave64) and their launch logic.
 //
-// One launch per tree level (Algorithm 1 visits tree edges in topological order;
-// rows of one level do not depend on each other).  A launch fuses the two stages
-// of Section 2.2: for each row x of the level
+// The compression tree is cut into vertical paths; a path is one work item, and the paths whose head
+// hangs off a row of a round-r path form round r + 1: one launch per round (Algorithm 1 visits tree
+// edges in topological order; work items of one round do not depend on each other).  A launch fuses
+// the two stages of Section 2.2: for each row x of a path
 //     Y[x,:] = Y[r_x,:] + sum_{j in Delta+} X[j,:] - sum_{j in Delta-} X[j,:]        (Eq. (5))
-// so a compressed row costs one parent-row read instead of a read-modify-write.
-// A group of LANES lanes owns one row and VEC consecutive columns per lane; a
-// wave carries 64/LANES rows.  Delta columns are fetched cooperatively (one
-// coalesced load per LANES entries) and broadcast inside the group.
+// with the running sum kept in registers from row to row, so a compressed row costs at most one
+// parent-row read, never a read-modify-write.  A group of LANES lanes owns one work item and VEC
+// consecutive columns per lane; a wave carries 64/LANES work items.  Entries are fetched
+// cooperatively (one coalesced load per LANES entries) and broadcast inside the group.
+// Long rows are cut into segments by column range, one range per XCD, summed by a combine launch.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
