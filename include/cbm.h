@@ -77,7 +77,11 @@ typedef enum {
  *                does not, and every row is then stored in full (the paper's
  *                own finding for its small citation graphs, Section 3.3); the
  *                same model drops a trailing round of dependent work when
- *                storing its rows in full is cheaper than its launch.  The
+ *                storing its rows in full is cheaper than its launch, and on a
+ *                matrix of 65536 rows or more the candidate search first looks
+ *                at every 64th row: if their best candidates would save under
+ *                2 % of their entries, the search stops there and every row is
+ *                stored in full.  The
  *                tree is cut into vertical paths, one work item each;
  *                dependent kernel launches per product = rounds of paths
  *                (cbm_stats), at most the depth.  Any value yields a valid CBM

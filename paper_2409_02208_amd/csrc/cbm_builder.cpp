@@ -27,6 +27,7 @@ namespace {
 constexpr int32_t kDefaultMaxDepth = 16;
 constexpr int32_t kDefaultHubCap = 512;
 constexpr int32_t kDefaultMaxCand = 8;
+constexpr int64_t kSampleMinRows = 65536;  // automatic mode samples the compressibility of matrices this large first
 constexpr int32_t kSplitLenDefault = 512;  // most delta entries in one segment of a split row
 constexpr int32_t kSplitMinDefault = 128;  // rows with more delta entries than this are split
 constexpr int32_t kPhasesDefault = 4;      // sub-ranges of an XCD's column range, for rows of >= kFineMin entries
@@ -140,6 +141,8 @@ struct Builder {
     std::vector<int64_t> optr;  // candidate edges bucketed by parent
     std::vector<int32_t> ochild, ow;
     bool device_candidates = false;  // run the candidate search on the GPU
+    bool sample_first = false;       // estimate what a tree could save from a sample of rows before the full search
+    bool skip_tree = false;          // the sample said: nothing to gain, store every row in full
     cbm_status find_candidates();
     void prim(int64_t seeds);
     void arborescence();
@@ -243,7 +246,99 @@ cbm_status Builder::find_candidates() {
     }
     lap("transpose");
 
-    // candidate parents: rows sharing columns, ranked by exact Hamming distance
+    // candidate parents of one row: rows sharing columns, ranked by exact Hamming distance (the best come out in sc)
+    struct Scored {
+        int64_t score;  // saving = nnz(a_x) - w(y,x) = 2|a_x n a_y| - nnz(a_y) (upper bound, then exact)
+        int32_t y;
+    };
+    auto row_candidates = [&](int64_t x, std::vector<int32_t>& cnt, std::vector<int32_t>& tch, std::vector<Scored>& sc) {
+        sc.clear();
+        const int64_t nx = rlen(x);
+        if (nx < 1) return;
+        tch.clear();
+        int64_t nhub = 0;
+        for (const int32_t* pj = row(x); pj != row(x) + nx; ++pj) {
+            int64_t deg = tptr[*pj + 1] - tptr[*pj];
+            if (hub_cap >= 0 && deg > hub_cap) {  // a hub column: too many rows to expand
+                ++nhub;
+                continue;
+            }
+            for (int64_t q = tptr[*pj]; q < tptr[*pj + 1]; ++q) {
+                int32_t y = trow[q];
+                if (cnt[y]++ == 0) tch.push_back(y);
+            }
+        }
+        for (int32_t y : tch) {
+            int64_t ipart = cnt[y];
+            cnt[y] = 0;
+            if (y == x) continue;
+            int64_t ny = rlen(y);
+            int64_t iub = ipart + std::min<int64_t>(nhub, std::min(ny, nx) - ipart);
+            int64_t ub = 2 * iub - ny;
+            if (ub >= min_saving) sc.push_back({ub, y});
+        }
+        if (sc.empty()) return;
+        auto better = [](const Scored& a, const Scored& b2) {
+            return a.score != b2.score ? a.score > b2.score : a.y < b2.y;
+        };
+        if (nhub > 0) {
+            // shared hub columns were not counted: settle the best few by exact intersection
+            size_t keep = max_cand < 0 ? sc.size() : std::min<size_t>(sc.size(), 2 * (size_t)max_cand);
+            if (keep < sc.size()) {
+                std::nth_element(sc.begin(), sc.begin() + keep, sc.end(), better);
+                sc.resize(keep);
+            }
+            size_t w = 0;
+            for (auto& s : sc) {
+                int64_t ny = rlen(s.y);
+                int64_t I = intersect_size(row(x), nx, row(s.y), ny);
+                s.score = 2 * I - ny;
+                if (s.score >= min_saving) sc[w++] = s;
+            }
+            sc.resize(w);
+        }
+        size_t keep = max_cand < 0 ? sc.size() : std::min<size_t>(sc.size(), (size_t)max_cand);
+        if (keep < sc.size()) {
+            std::nth_element(sc.begin(), sc.begin() + keep, sc.end(), better);
+            sc.resize(keep);
+        }
+    };
+    std::vector<std::vector<int32_t>> counters(nthreads), touched(nthreads);
+
+    // Automatic mode on a large matrix: look at every 64th row first.  The best candidate of a row bounds what any
+    // tree can save on it; if the sample says the whole matrix would shed under 2 % of its entries, no tree can pay
+    // for a dependent launch, and the full search (the bulk of the build time) is skipped.
+    if (sample_first) {
+        const int64_t stride = 64, nsample = (m + stride - 1) / stride;
+        std::vector<int64_t> saved(nthreads, 0), seen(nthreads, 0);
+        parallel_chunks(nthreads, nsample, 16, [&](int64_t b, int64_t e, int tid) {
+            auto& cnt = counters[tid];
+            if (cnt.empty()) cnt.assign(m, 0);
+            std::vector<Scored> sc;
+            for (int64_t i = b; i < e; ++i) {
+                const int64_t x = i * stride;
+                row_candidates(x, cnt, touched[tid], sc);
+                int64_t best = 0;
+                for (auto& c : sc) best = std::max(best, c.score);
+                saved[tid] += best;
+                seen[tid] += rlen(x);
+            }
+        });
+        int64_t sv = 0, sn = 0;
+        for (int t = 0; t < nthreads; ++t) {
+            sv += saved[t];
+            sn += seen[t];
+        }
+        if (verbose)
+            std::fprintf(stderr, "[cbm_build] sample of %ld rows: at most %.2f %% of their entries can be saved\n", (long)nsample,
+                         sn > 0 ? 100.0 * sv / sn : 0.0);
+        lap("candidate sample");
+        if (sv * 50 < sn) {
+            skip_tree = true;
+            return CBM_OK;
+        }
+    }
+
     std::vector<std::vector<Cand>> cand_per_thread(nthreads);
     if (device_candidates) {
         std::vector<int32_t> cn, cy, cw;
@@ -254,69 +349,15 @@ cbm_status Builder::find_candidates() {
         for (int64_t x = 0; x < m; ++x)
             for (int32_t i = 0; i < cn[x]; ++i) out.push_back({(int32_t)x, cy[x * max_cand + i], cw[x * max_cand + i]});
     } else {
-        std::vector<std::vector<int32_t>> counters(nthreads), touched(nthreads);
         parallel_chunks(nthreads, m, 64, [&](int64_t b, int64_t e, int tid) {
             auto& cnt = counters[tid];
-            auto& tch = touched[tid];
             auto& out = cand_per_thread[tid];
             if (cnt.empty()) cnt.assign(m, 0);
-            struct Scored {
-                int64_t score;  // saving = nnz(a_x) - w(y,x) = 2|a_x n a_y| - nnz(a_y) (upper bound, then exact)
-                int32_t y;
-            };
             std::vector<Scored> sc;
             for (int64_t x = b; x < e; ++x) {
+                row_candidates(x, cnt, touched[tid], sc);
                 const int64_t nx = rlen(x);
-                if (nx < 1) continue;
-                tch.clear();
-                int64_t nhub = 0;
-                for (const int32_t* pj = row(x); pj != row(x) + nx; ++pj) {
-                    int64_t deg = tptr[*pj + 1] - tptr[*pj];
-                    if (hub_cap >= 0 && deg > hub_cap) {  // a hub column: too many rows to expand
-                        ++nhub;
-                        continue;
-                    }
-                    for (int64_t q = tptr[*pj]; q < tptr[*pj + 1]; ++q) {
-                        int32_t y = trow[q];
-                        if (cnt[y]++ == 0) tch.push_back(y);
-                    }
-                }
-                sc.clear();
-                for (int32_t y : tch) {
-                    int64_t ipart = cnt[y];
-                    cnt[y] = 0;
-                    if (y == x) continue;
-                    int64_t ny = rlen(y);
-                    int64_t iub = ipart + std::min<int64_t>(nhub, std::min(ny, nx) - ipart);
-                    int64_t ub = 2 * iub - ny;
-                    if (ub >= min_saving) sc.push_back({ub, y});
-                }
-                if (sc.empty()) continue;
-                auto better = [](const Scored& a, const Scored& b2) {
-                    return a.score != b2.score ? a.score > b2.score : a.y < b2.y;
-                };
-                if (nhub > 0) {
-                    // shared hub columns were not counted: settle the best few by exact intersection
-                    size_t keep = max_cand < 0 ? sc.size() : std::min<size_t>(sc.size(), 2 * (size_t)max_cand);
-                    if (keep < sc.size()) {
-                        std::nth_element(sc.begin(), sc.begin() + keep, sc.end(), better);
-                        sc.resize(keep);
-                    }
-                    size_t w = 0;
-                    for (auto& s : sc) {
-                        int64_t ny = rlen(s.y);
-                        int64_t I = intersect_size(row(x), nx, row(s.y), ny);
-                        s.score = 2 * I - ny;
-                        if (s.score >= min_saving) sc[w++] = s;
-                    }
-                    sc.resize(w);
-                }
-                size_t keep = max_cand < 0 ? sc.size() : std::min<size_t>(sc.size(), (size_t)max_cand);
-                if (keep < sc.size()) {
-                    std::nth_element(sc.begin(), sc.begin() + keep, sc.end(), better);
-                    sc.resize(keep);
-                }
-                for (auto& s : sc) out.push_back({(int32_t)x, s.y, (int32_t)(nx - s.score)});
+                for (auto& c : sc) out.push_back({(int32_t)x, c.y, (int32_t)(nx - c.score)});
             }
         });
     }
@@ -948,7 +989,11 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
         }
         B.lap("exact arborescence");
     } else if (tree) {
+        B.sample_first = B.auto_depth && m >= kSampleMinRows && !std::getenv("CBM_NO_SAMPLE");
         if ((st = B.find_candidates()) != CBM_OK) return st;
+    }
+    if (tree && !exact_tree && B.skip_tree) tree = false;
+    if (tree && !exact_tree) {
         const int64_t forced_len = env_or("CBM_PATH_MAX", 0);
         const int64_t forced_seeds = o.seed_roots > 0 ? o.seed_roots : o.seed_roots < 0 ? 0 : env_or("CBM_SEED_ROOTS", -1);
         double best_us = 1e300;
@@ -993,7 +1038,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
             }
         }
         B.lap("tree + path model");
-    } else {
+    } else if (!tree) {
         B.all_roots();
         double best_us = 1e300;
         for (int64_t split : split_choices) {
