@@ -266,3 +266,40 @@ def test_transposed_build_holds_the_transpose(self_loops):
     assert (s["m"], s["n"], s["nnz"]) == (n, m, At.nnz)
     _check_invariants(n, m, At.indptr.astype(np.int64), At.indices.astype(np.int32), h, 1, False)
     cbm.cbm_free(h)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_invariants_random_options(seed):
+    """Seeded sweep over shapes, structure and every build option: the format must decompress to the input and
+    keep Properties 1 and 2, the alpha rule and the draw rule whatever the options."""
+    rng = np.random.default_rng(500 + seed)
+    m = int(rng.integers(1, 400))
+    square = bool(rng.integers(0, 2))
+    n = m if square else int(rng.integers(1, 400))
+    rows, base = [], None
+    for _ in range(m):
+        kind = int(rng.integers(0, 8))
+        if kind == 0:
+            r = []
+        elif kind == 1 and base is not None:
+            r = list(base)
+        elif kind in (2, 3) and base is not None and len(base) > 2:
+            r = sorted(set(base[:-1]) | set(rng.integers(0, n, size=2).tolist()))
+        elif kind == 4 and n > 150:
+            r = sorted(rng.choice(n, size=int(rng.integers(130, n)), replace=False).tolist())   # long enough to be split
+        else:
+            r = sorted(set(rng.integers(0, n, size=int(rng.integers(1, 30))).tolist()))
+        rows.append(r)
+        if r and rng.random() < 0.4:
+            base = r
+    rowptr, colidx = _csr(rows)
+    alpha = int(rng.choice([0, 1, 2, 7]))
+    self_loops = square and bool(rng.integers(0, 2))
+    opts = dict(max_depth=int(rng.choice([-1, 2, 5, 16])), hub_cap=int(rng.choice([0, 3, -1])),
+                max_candidates=int(rng.choice([0, 1, -1])), seed_roots=int(rng.choice([0, -1, 4])),
+                exact_tree=bool(rng.integers(0, 3) == 0), num_threads=int(rng.choice([0, 1, 3])))
+    h = cbm.cbm_build(m, n, rowptr, colidx, alpha=alpha, add_self_loops=self_loops, host_only=True, **opts)
+    s = _check_invariants(m, n, rowptr, colidx, h, alpha, self_loops)
+    if opts["max_depth"] > 0 and not opts["exact_tree"]:
+        assert s["depth"] <= opts["max_depth"]
+    cbm.cbm_free(h)
