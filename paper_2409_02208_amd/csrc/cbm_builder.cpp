@@ -98,6 +98,48 @@ int64_t intersect_size(const int32_t* a, int64_t na, const int32_t* b, int64_t n
     return c;
 }
 
+// Transpose of a CSR pattern (fewer than 2^32 entries): tptr / trow = rows holding each column, ascending inside a
+// column.  A counting sort whose row blocks (equal shares of the entries, in row order) are counted and scattered by
+// one thread each; a block's start inside a column is the column's start plus what the earlier blocks put there.
+void transpose_pattern(int nthreads, int64_t m, int64_t n, const int64_t* rowptr, const int32_t* colidx,
+                       std::vector<int64_t>& tptr, std::vector<int32_t>& trow) {
+    const int64_t nz = rowptr[m];
+    tptr.assign(n + 1, 0);
+    trow.resize(nz);
+    int nt = nz < (1 << 20) ? 1 : std::max(1, std::min(nthreads, 64));
+    while (nt > 1 && (int64_t)nt * n * 4 > ((int64_t)1 << 30)) --nt;  // at most 1 GiB of per-block offsets
+    std::vector<int64_t> rb(nt + 1, m);
+    rb[0] = 0;
+    for (int t = 1; t < nt; ++t) rb[t] = std::lower_bound(rowptr, rowptr + m + 1, nz * t / nt) - rowptr;
+    std::vector<std::vector<uint32_t>> off(nt);
+    auto run = [&](auto&& fn) {
+        if (nt == 1) {
+            fn(0);
+            return;
+        }
+        std::vector<std::thread> pool;
+        for (int t = 0; t < nt; ++t) pool.emplace_back(fn, t);
+        for (auto& th : pool) th.join();
+    };
+    run([&](int t) {
+        off[t].assign(n, 0);
+        for (int64_t p = rowptr[rb[t]]; p < rowptr[rb[t + 1]]; ++p) ++off[t][colidx[p]];
+    });
+    for (int64_t j = 0; j < n; ++j) {
+        int64_t at = tptr[j];
+        for (int t = 0; t < nt; ++t) {
+            const uint32_t c = off[t][j];
+            off[t][j] = (uint32_t)at;
+            at += c;
+        }
+        tptr[j + 1] = at;
+    }
+    run([&](int t) {
+        for (int64_t i = rb[t]; i < rb[t + 1]; ++i)
+            for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) trow[off[t][colidx[p]]++] = (int32_t)i;
+    });
+}
+
 struct Cand {
     int32_t child, parent, w;
 };
@@ -208,16 +250,9 @@ void Builder::self_loops(const int64_t* in_rowptr, const int32_t* in_colidx) {
 
 // Replace the matrix by its transpose (n x m).  Rows are scanned in order, so every new row comes out sorted.
 void Builder::transpose_matrix() {
-    std::vector<int64_t> tp(n + 1, 0);
-    const int64_t nz = rowptr[m];
-    for (int64_t p = 0; p < nz; ++p) ++tp[colidx[p] + 1];
-    for (int64_t j = 0; j < n; ++j) tp[j + 1] += tp[j];
-    std::vector<int32_t> tc(nz);
-    {
-        std::vector<int64_t> fill(tp.begin(), tp.end() - 1);
-        for (int64_t i = 0; i < m; ++i)
-            for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) tc[fill[colidx[p]]++] = (int32_t)i;
-    }
+    std::vector<int64_t> tp;
+    std::vector<int32_t> tc;
+    transpose_pattern(nthreads, m, n, rowptr, colidx, tp, tc);
     own_rowptr.swap(tp);
     own_colidx.swap(tc);
     rowptr = own_rowptr.data();
@@ -235,15 +270,9 @@ void Builder::all_roots() {
 // Candidate parents: for every row, the rows that share columns with it, ranked by exact Hamming distance.
 cbm_status Builder::find_candidates() {
     // transpose: rows holding each column
-    std::vector<int64_t> tptr(n + 1, 0);
-    std::vector<int32_t> trow(nnz);
-    for (int64_t p = 0; p < nnz; ++p) ++tptr[colidx[p] + 1];
-    for (int64_t j = 0; j < n; ++j) tptr[j + 1] += tptr[j];
-    {
-        std::vector<int64_t> fill(tptr.begin(), tptr.end() - 1);
-        for (int64_t i = 0; i < m; ++i)
-            for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) trow[fill[colidx[p]]++] = (int32_t)i;
-    }
+    std::vector<int64_t> tptr;
+    std::vector<int32_t> trow;
+    transpose_pattern(nthreads, m, n, rowptr, colidx, tptr, trow);
     lap("transpose");
 
     // candidate parents of one row: rows sharing columns, ranked by exact Hamming distance (the best come out in sc)
