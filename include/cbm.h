@@ -159,9 +159,10 @@ cbm_status cbm_build(int64_t m, int64_t n, const int64_t* rowptr, const int32_t*
  *       kernels and returns; the caller synchronises.
  * If the handle was built with add_self_loops the product is (A v I) . X.
  * k not a multiple of 4, or pointers / leading dimensions that are not 16-byte
- * multiples, select a narrower-load variant of the same kernel, not an error --
- * but a slow one (about 2.5x the time per byte on a large graph): pad the
- * feature dimension to a multiple of 4 where speed matters.
+ * multiples, select a variant of the same kernel that moves 32 bits per lane
+ * and access instead of 128, not an error; it takes about 1.7x the time per
+ * byte on a large graph, so pad the feature dimension to a multiple of 4 where
+ * speed matters.
  * Not thread-safe per handle (rows with very long delta lists use scratch owned
  * by the handle, sized on first use for a given k).
  */

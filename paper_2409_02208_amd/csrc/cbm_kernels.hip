@@ -6,8 +6,8 @@
 // the two stages of Section 2.2: for each row x of a path
 //     Y[x,:] = Y[r_x,:] + sum_{j in Delta+} X[j,:] - sum_{j in Delta-} X[j,:]        (Eq. (5))
 // with the running sum kept in registers from row to row, so a compressed row costs at most one
-// parent-row read, never a read-modify-write.  A group of LANES lanes owns one work item and VEC
-// consecutive columns per lane; a wave carries 64/LANES work items.  Entries are fetched
+// parent-row read, never a read-modify-write.  A group of LANES lanes owns one work item and four
+// columns per lane; a wave carries 64/LANES work items.  Entries are fetched
 // cooperatively (one coalesced load per LANES entries) and broadcast inside the group.
 // Long rows are cut into segments by column range, one range per XCD, summed by a combine launch.
 #include <hip/hip_runtime.h>
@@ -29,42 +29,49 @@
 
 namespace {
 
-template <int VEC>
-struct Vec;
-template <>
-struct Vec<1> {
-    float v[1];
-};
-template <>
-struct alignas(8) Vec<2> {
-    float v[2];
-};
-template <>
-struct alignas(16) Vec<4> {
+// Four columns of a row: what one lane holds.
+struct alignas(16) Vec4 {
     float v[4];
 };
+typedef float float4a __attribute__((ext_vector_type(4)));
 
-template <int VEC>
-__device__ __forceinline__ Vec<VEC> ld(const float* p) {
-    return *reinterpret_cast<const Vec<VEC>*>(p);
-}
-template <int VEC>
-__device__ __forceinline__ void st(float* p, const Vec<VEC>& x) {
-    *reinterpret_cast<Vec<VEC>*>(p) = x;
+// Which four columns a lane holds, and how it moves them.
+// RAGGED = false: k is a multiple of 4 and every row starts on a 16-byte boundary; lane l of a group holds the
+// consecutive columns 4l .. 4l+3 of the group's column chunk: one aligned 128-bit access.
+// RAGGED = true: any k, leading dimension and base address; lane l holds columns l, l + LANES, l + 2 LANES,
+// l + 3 LANES of the chunk, so every access is a 32-bit one that the group's lanes make to consecutive words.
+template <bool RAGGED, int LANES>
+__device__ __forceinline__ Vec4 ld_row(const float* row, int c0, int k) {
+    Vec4 r;
+    if (!RAGGED) {
+        const float4a t = *reinterpret_cast<const float4a*>(row + c0);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) r.v[c] = t[c];
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) r.v[c] = c0 + c * LANES < k ? row[c0 + c * LANES] : 0.0f;
+    }
+    return r;
 }
 // Streaming store: rows of Y and partial sums are written once and not re-read by the same launch, so
 // they should not displace the gathered rows of X from L2.
-template <int VEC>
-__device__ __forceinline__ void st_stream(float* p, const Vec<VEC>& x) {
-    typedef float vec_t __attribute__((ext_vector_type(VEC)));
-    vec_t v;
+template <bool RAGGED, int LANES>
+__device__ __forceinline__ void st_row(float* row, int c0, int k, const Vec4& x) {
+    if (!RAGGED) {
+        float4a t;
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) v[c] = x.v[c];
-    __builtin_nontemporal_store(v, reinterpret_cast<vec_t*>(p));
+        for (int c = 0; c < 4; ++c) t[c] = x.v[c];
+        __builtin_nontemporal_store(t, reinterpret_cast<float4a*>(row + c0));
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (c0 + c * LANES < k) __builtin_nontemporal_store(x.v[c], row + c0 + c * LANES);
+    }
 }
-template <>
-__device__ __forceinline__ void st_stream<1>(float* p, const Vec<1>& x) {
-    __builtin_nontemporal_store(x.v[0], p);
+// first column of lane `sl` in column chunk `chunk` (a chunk = 4 LANES columns either way)
+template <bool RAGGED, int LANES>
+__device__ __forceinline__ int first_column(int chunk, int sl) {
+    return RAGGED ? chunk * 4 * LANES + sl : (chunk * LANES + sl) * 4;
 }
 
 // MODE 0: Y = M X (M = the compressed matrix).
@@ -86,17 +93,18 @@ struct Mode {
 };
 
 // out = finish(acc): acc (+ self_w * own X row) (* row weight) (then ReLU)
-template <int VEC, int MODE>
-__device__ __forceinline__ void store_row(float* dst, Vec<VEC> acc, bool finish, float w, const Vec<VEC>& own, float self_w) {
+template <bool RAGGED, int LANES, int MODE>
+__device__ __forceinline__ void store_row(float* row, int c0, int k, Vec4 acc, bool finish, float w, const Vec4& own,
+                                          float self_w) {
     if (finish) {
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) {
+        for (int c = 0; c < 4; ++c) {
             if (Mode<MODE>::self) acc.v[c] = fmaf(self_w, own.v[c], acc.v[c]);
             if (Mode<MODE>::wrow) acc.v[c] *= w;
             if (Mode<MODE>::relu) acc.v[c] = fmaxf(acc.v[c], 0.0f);
         }
     }
-    st_stream<VEC>(dst, acc);
+    st_row<RAGGED, LANES>(row, c0, k, acc);
 }
 
 // One work item = one path of the compression tree (or one segment of a split row): start from
@@ -120,14 +128,14 @@ struct CbmSegMap {
 
 // Waves per SIMD the register allocation is held to: 4 with batches of 8 rows, 6 with batches of 4 --
 // one less for the few variants that would otherwise spill registers.
-constexpr int level_min_waves(int vec, int lanes, int mode, int umax) {
+constexpr int level_min_waves(bool ragged, int lanes, int mode, int umax) {
     const bool weighted = mode >= 1 && mode <= 3;
-    if (umax >= 8) return (vec == 4 && lanes == 16 && weighted) ? 3 : 4;
-    return (vec == 4 && lanes == 8 && weighted) ? 5 : 6;
+    if (umax >= 8) return ((lanes == 16 || (ragged && lanes == 8)) && weighted) ? 3 : 4;
+    return (lanes == 8 && weighted) ? 5 : 6;
 }
 
-template <int VEC, int LANES, int MODE, int UMAX>
-__global__ __launch_bounds__(256, level_min_waves(VEC, LANES, MODE, UMAX)) void cbm_level_kernel(const CbmTask* __restrict__ tasks, int64_t ntasks,
+template <bool RAGGED, int LANES, int MODE, int UMAX>
+__global__ __launch_bounds__(256, level_min_waves(RAGGED, LANES, MODE, UMAX)) void cbm_level_kernel(const CbmTask* __restrict__ tasks, int64_t ntasks,
                                                         const CbmSegMap map,
                                                         const uint32_t* __restrict__ stream,
                                                         const float* __restrict__ X, int64_t ldx, float* Y,
@@ -153,13 +161,13 @@ __global__ __launch_bounds__(256, level_min_waves(VEC, LANES, MODE, UMAX)) void 
     }
     const CbmTask tk = tasks[t];
     const uint32_t len = tk.len_flags & CBM_TASK_LEN_MASK;
-    const int c0 = (blockIdx.y * LANES + sl) * VEC;
+    const int c0 = first_column<RAGGED, LANES>(blockIdx.y, sl);
     const bool colok = c0 < k;
 
-    Vec<VEC> acc;
+    Vec4 acc;
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) acc.v[c] = 0.0f;
-    if (tk.parent >= 0 && colok) acc = ld<VEC>(Y + (int64_t)tk.parent * ldy + c0);
+    for (int c = 0; c < 4; ++c) acc.v[c] = 0.0f;
+    if (tk.parent >= 0 && colok) acc = ld_row<RAGGED, LANES>(Y + (int64_t)tk.parent * ldy, c0, k);
 
     const uint32_t* es = stream + tk.start;
     // lanes past the end of the stream hold entry 0 with weight 0: a delta that is never loaded
@@ -181,7 +189,7 @@ __global__ __launch_bounds__(256, level_min_waves(VEC, LANES, MODE, UMAX)) void 
     int cur = 0;         // chunk whose entries are in e0 / w0
 
     struct Batch {
-        Vec<VEC> x[U];
+        Vec4 x[U];
         uint32_t e[U];
     };
     const int nb = (int)((len + U - 1) / U);
@@ -204,10 +212,10 @@ __global__ __launch_bounds__(256, level_min_waves(VEC, LANES, MODE, UMAX)) void 
             const bool gather = !(S.e[u] & CBM_ENTRY_MARK) ||
                                 (M::self && !(S.e[u] & CBM_ENTRY_INTERNAL));
             if ((uint32_t)(b * U + u) < len && gather && colok) {
-                S.x[u] = ld<VEC>(X + (int64_t)(S.e[u] & CBM_ENTRY_INDEX_MASK) * ldx + c0);
+                S.x[u] = ld_row<RAGGED, LANES>(X + (int64_t)(S.e[u] & CBM_ENTRY_INDEX_MASK) * ldx, c0, k);
             } else {
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) S.x[u].v[c] = 0.0f;
+                for (int c = 0; c < 4; ++c) S.x[u].v[c] = 0.0f;
             }
         }
     };
@@ -220,15 +228,15 @@ __global__ __launch_bounds__(256, level_min_waves(VEC, LANES, MODE, UMAX)) void 
             const float w = M::weights ? __shfl(wsrc, off + u, LANES) : 0.0f;
             if (S.e[u] & CBM_ENTRY_MARK) {
                 if (colok)
-                    store_row<VEC, MODE>(Y + (int64_t)(S.e[u] & CBM_ENTRY_INDEX_MASK) * ldy + c0, acc,
-                                         !(S.e[u] & CBM_ENTRY_INTERNAL), w, S.x[u], self_w);
+                    store_row<RAGGED, LANES, MODE>(Y + (int64_t)(S.e[u] & CBM_ENTRY_INDEX_MASK) * ldy, c0, k, acc,
+                                                   !(S.e[u] & CBM_ENTRY_INTERNAL), w, S.x[u], self_w);
             } else if (M::wcol) {
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(w, S.x[u].v[c], acc.v[c]);
+                for (int c = 0; c < 4; ++c) acc.v[c] = fmaf(w, S.x[u].v[c], acc.v[c]);
             } else {
                 const uint32_t sgn = S.e[u] & CBM_DELTA_MINUS;
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) acc.v[c] += __uint_as_float(__float_as_uint(S.x[u].v[c]) ^ sgn);
+                for (int c = 0; c < 4; ++c) acc.v[c] += __uint_as_float(__float_as_uint(S.x[u].v[c]) ^ sgn);
             }
         }
     };
@@ -240,11 +248,13 @@ __global__ __launch_bounds__(256, level_min_waves(VEC, LANES, MODE, UMAX)) void 
         if (b + 2 < nb) fetch(A, b + 2);
         if (b + 1 < nb) consume(B, b + 1);
     }
-    if ((tk.len_flags & CBM_TASK_SEGMENT) && colok) st_stream<VEC>(scratch + (int64_t)tk.row * ld_scratch + c0, acc);
+    // scratch rows (16-byte aligned, padded to a multiple of four columns) use the same lane-to-column map
+    if ((tk.len_flags & CBM_TASK_SEGMENT) && colok)
+        st_row<RAGGED, LANES>(scratch + (int64_t)tk.row * ld_scratch, c0, k, acc);
 }
 
 // Rows whose delta list was cut into segments: Y[x,:] = Y[r_x,:] + sum of the row's segment sums.
-template <int VEC, int LANES, int MODE>
+template <bool RAGGED, int LANES, int MODE>
 __global__ __launch_bounds__(256) void cbm_combine_kernel(const CbmTask* __restrict__ comb, int64_t ncomb,
                                                           const float* __restrict__ X, int64_t ldx, float* Y,
                                                           int64_t ldy, const float* scratch, int64_t ld_scratch,
@@ -252,37 +262,38 @@ __global__ __launch_bounds__(256) void cbm_combine_kernel(const CbmTask* __restr
     constexpr int G = 64 / LANES;
     const int lane = threadIdx.x & 63;
     const int64_t t = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * G + lane / LANES;
-    const int c0 = (blockIdx.y * LANES + lane % LANES) * VEC;
+    const int c0 = first_column<RAGGED, LANES>(blockIdx.y, lane % LANES);
     if (t >= ncomb || c0 >= k) return;
     const CbmTask tk = comb[t];
     const uint32_t nseg = tk.len_flags & CBM_TASK_LEN_MASK;
-    Vec<VEC> acc;
+    Vec4 acc;
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) acc.v[c] = 0.0f;
-    if (tk.parent >= 0) acc = ld<VEC>(Y + (int64_t)tk.parent * ldy + c0);
-    const float* part = scratch + (int64_t)tk.start * ld_scratch + c0;
+    for (int c = 0; c < 4; ++c) acc.v[c] = 0.0f;
+    if (tk.parent >= 0) acc = ld_row<RAGGED, LANES>(Y + (int64_t)tk.parent * ldy, c0, k);
+    const float* part = scratch + (int64_t)tk.start * ld_scratch;
     for (uint32_t s0 = 0; s0 < nseg; s0 += 8) {  // eight independent loads in flight, added in segment order
-        Vec<VEC> p[8];
+        Vec4 p[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             if (s0 + u < nseg) {
-                p[u] = ld<VEC>(part + (int64_t)(s0 + u) * ld_scratch);
+                p[u] = ld_row<RAGGED, LANES>(part + (int64_t)(s0 + u) * ld_scratch, c0, k);
             } else {
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) p[u].v[c] = 0.0f;
+                for (int c = 0; c < 4; ++c) p[u].v[c] = 0.0f;
             }
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u)
 #pragma unroll
-            for (int c = 0; c < VEC; ++c) acc.v[c] += p[u].v[c];
+            for (int c = 0; c < 4; ++c) acc.v[c] += p[u].v[c];
     }
     const bool finish = !(tk.len_flags & CBM_TASK_INTERNAL);
-    Vec<VEC> own;
+    Vec4 own;
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) own.v[c] = 0.0f;
-    if (Mode<MODE>::self && finish) own = ld<VEC>(X + (int64_t)tk.row * ldx + c0);
-    store_row<VEC, MODE>(Y + (int64_t)tk.row * ldy + c0, acc, finish, Mode<MODE>::wrow ? rw[tk.row] : 1.0f, own, self_w);
+    for (int c = 0; c < 4; ++c) own.v[c] = 0.0f;
+    if (Mode<MODE>::self && finish) own = ld_row<RAGGED, LANES>(X + (int64_t)tk.row * ldx, c0, k);
+    store_row<RAGGED, LANES, MODE>(Y + (int64_t)tk.row * ldy, c0, k, acc, finish, Mode<MODE>::wrow ? rw[tk.row] : 1.0f, own,
+                                   self_w);
 }
 
 // Deferred finish of the rows other work items were compressed against: row weight (MODE 1-3) or self term (MODE 4).
@@ -333,23 +344,23 @@ struct LaunchCtx {
     float self_w;     // MODE 4
 };
 
-template <int VEC, int LANES, int MODE, int UMAX>
+template <bool RAGGED, int LANES, int MODE, int UMAX>
 void launch_level(const LaunchCtx& c, const CbmLevel& L) {
     constexpr int G = 64 / LANES;
-    const int ychunks = (c.k + LANES * VEC - 1) / (LANES * VEC);
+    const int ychunks = (c.k + LANES * 4 - 1) / (LANES * 4);
     CbmSegMap map{};
     if (L.task_count > 0) {
         dim3 grid((unsigned)((L.task_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
-        hipLaunchKernelGGL((cbm_level_kernel<VEC, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream,
+        hipLaunchKernelGGL((cbm_level_kernel<RAGGED, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream,
                            c.h->d_tasks + L.task_begin, L.task_count, map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy,
                            c.h->d_scratch, c.ld_scratch, c.ws, c.rw, c.self_w, c.k);
     }
 }
 // all segments of all split rows, one block of work items per XCD
-template <int VEC, int LANES, int MODE, int UMAX>
+template <bool RAGGED, int LANES, int MODE, int UMAX>
 void launch_segments(const LaunchCtx& c, const CbmLevel&) {
     constexpr int G = 64 / LANES;
-    const int ychunks = (c.k + LANES * VEC - 1) / (LANES * VEC);
+    const int ychunks = (c.k + LANES * 4 - 1) / (LANES * 4);
     CbmSegMap map{};
     int64_t most = 0;
     for (int j = 0; j < CBM_XCD; ++j) {
@@ -359,16 +370,16 @@ void launch_segments(const LaunchCtx& c, const CbmLevel&) {
     }
     map.use = 1;
     dim3 grid((unsigned)(CBM_XCD * ((most + 4 * G - 1) / (4 * G))), (unsigned)ychunks);
-    hipLaunchKernelGGL((cbm_level_kernel<VEC, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream, c.h->d_tasks,
+    hipLaunchKernelGGL((cbm_level_kernel<RAGGED, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream, c.h->d_tasks,
                        (int64_t)c.h->tasks.size(), map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.h->d_scratch,
                        c.ld_scratch, c.ws, c.rw, c.self_w, c.k);
 }
-template <int VEC, int LANES, int MODE>
+template <bool RAGGED, int LANES, int MODE>
 void launch_combine(const LaunchCtx& c, const CbmLevel& L) {
     constexpr int G = 64 / LANES;
-    const int ychunks = (c.k + LANES * VEC - 1) / (LANES * VEC);
+    const int ychunks = (c.k + LANES * 4 - 1) / (LANES * 4);
     dim3 grid((unsigned)((L.comb_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
-    hipLaunchKernelGGL((cbm_combine_kernel<VEC, LANES, MODE>), grid, dim3(256), 0, c.stream,
+    hipLaunchKernelGGL((cbm_combine_kernel<RAGGED, LANES, MODE>), grid, dim3(256), 0, c.stream,
                        c.h->d_comb + L.comb_begin, L.comb_count, c.X, c.ldx, c.Y, c.ldy, c.h->d_scratch,
                        c.ld_scratch, c.rw, c.self_w, c.k);
 }
@@ -380,28 +391,28 @@ struct Variant {
     int group;                          // work items per wave
 };
 
-template <int VEC, int LANES, int MODE>
+template <bool RAGGED, int LANES, int MODE>
 Variant variant() {
-    return {launch_level<VEC, LANES, MODE, 8>,    launch_combine<VEC, LANES, MODE>, launch_segments<VEC, LANES, MODE, 8>,
-            launch_level<VEC, LANES, MODE, 4>,    launch_segments<VEC, LANES, MODE, 4>, 64 / LANES};
+    return {launch_level<RAGGED, LANES, MODE, 8>, launch_combine<RAGGED, LANES, MODE>, launch_segments<RAGGED, LANES, MODE, 8>,
+            launch_level<RAGGED, LANES, MODE, 4>, launch_segments<RAGGED, LANES, MODE, 4>, 64 / LANES};
 }
-template <int VEC, int LANES>
+template <bool RAGGED, int LANES>
 Variant pick_mode(int mode) {
     switch (mode) {
-        case 0: return variant<VEC, LANES, 0>();
-        case 1: return variant<VEC, LANES, 1>();
-        case 2: return variant<VEC, LANES, 2>();
-        case 3: return variant<VEC, LANES, 3>();
-        default: return variant<VEC, LANES, 4>();
+        case 0: return variant<RAGGED, LANES, 0>();
+        case 1: return variant<RAGGED, LANES, 1>();
+        case 2: return variant<RAGGED, LANES, 2>();
+        case 3: return variant<RAGGED, LANES, 3>();
+        default: return variant<RAGGED, LANES, 4>();
     }
 }
-template <int VEC>
+template <bool RAGGED>
 Variant pick_lanes(int lanes, int mode) {
     switch (lanes) {
-        case 8: return pick_mode<VEC, 8>(mode);
-        case 16: return pick_mode<VEC, 16>(mode);
-        case 32: return pick_mode<VEC, 32>(mode);
-        default: return pick_mode<VEC, 64>(mode);
+        case 8: return pick_mode<RAGGED, 8>(mode);
+        case 16: return pick_mode<RAGGED, 16>(mode);
+        case 32: return pick_mode<RAGGED, 32>(mode);
+        default: return pick_mode<RAGGED, 64>(mode);
     }
 }
 
@@ -514,19 +525,15 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
         h->scratch_k = ld_scratch;
     }
 
-    // widest loads the operands allow
-    auto aligned = [&](int v) {
-        const uintptr_t mask = (uintptr_t)v * 4 - 1;
-        return k % v == 0 && ldx % v == 0 && ldy % v == 0 && ((uintptr_t)X & mask) == 0 && ((uintptr_t)Y & mask) == 0;
-    };
-    const int vec = aligned(4) ? 4 : aligned(2) ? 2 : 1;
+    // every lane holds four columns; rows that all start on 16-byte boundaries and hold a multiple of four columns
+    // take the aligned variant (128-bit accesses), anything else the ragged one (32-bit accesses, strided columns)
+    const bool aligned = k % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && ((uintptr_t)X & 15) == 0 && ((uintptr_t)Y & 15) == 0;
     // at least 8 lanes per work item, idle ones included: entries are fetched a group's width at a time, and groups
     // of 4 spend more on that than they save (k <= 16: 25-30 % slower, measured)
     int lanes = 8;
-    while (lanes < 64 && lanes * vec < k) lanes *= 2;
+    while (lanes < 64 && lanes * 4 < k) lanes *= 2;
     const int mode = (int)epi;
-    const Variant var = vec == 4 ? pick_lanes<4>(lanes, mode) : vec == 2 ? pick_lanes<2>(lanes, mode)
-                                                                         : pick_lanes<1>(lanes, mode);
+    const Variant var = aligned ? pick_lanes<false>(lanes, mode) : pick_lanes<true>(lanes, mode);
     if (h->profiling) {
         for (void* e : h->prof_events) hipEventDestroy((hipEvent_t)e);
         h->prof_events.clear();
@@ -537,7 +544,7 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
         const char* e = std::getenv("CBM_MANY_WAVES");
         return e ? std::atoll(e) : (int64_t)kManyWavesDefault;
     }();
-    const int64_t ychunks = ((int64_t)k + lanes * vec - 1) / (lanes * vec);
+    const int64_t ychunks = ((int64_t)k + lanes * 4 - 1) / (lanes * 4);
     auto many = [&](int64_t items) { return items / var.group * ychunks >= many_waves; };
     const bool wcol = mode == 1 || mode == 2, wrow = wcol || mode == 3;
     const LaunchCtx ctx{h, X, ldx, k, Y, ldy, ld_scratch, stream, h->d_wstream, mode == 3 ? h->d_rinv : h->d_dinv, self_weight};
