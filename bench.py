@@ -74,6 +74,29 @@ def device_copy_gbs(torch, nbytes=1 << 30, reps=5):
     return 2 * nbytes / ms / 1e6
 
 
+def vendor_csr_ms(torch, g, Xd, steps, warmup):
+    """The same normalised product as a CSR SpMM of the vendor's sparse library through torch.sparse (fp32 values
+    d_i^-1/2 d_j^-1/2, int64 indices): outside context for the report, or None if this PyTorch cannot do it."""
+    try:
+        n = g.n
+        rows = np.repeat(np.arange(n, dtype=np.int64), np.diff(g.rowptr))
+        r = np.concatenate((rows, np.arange(n, dtype=np.int64)))           # A + I (the generators emit no self loops)
+        c = np.concatenate((g.colidx.astype(np.int64), np.arange(n, dtype=np.int64)))
+        order = np.lexsort((c, r))
+        r, c = r[order], c[order]
+        d = np.bincount(r, minlength=n).astype(np.float64)
+        vals = (1.0 / np.sqrt(d[r] * d[c])).astype(np.float32)
+        crow = np.zeros(n + 1, dtype=np.int64)
+        np.cumsum(np.bincount(r, minlength=n), out=crow[1:])
+        A = torch.sparse_csr_tensor(torch.from_numpy(crow), torch.from_numpy(c), torch.from_numpy(vals), size=(n, n)).cuda()
+        ms = time_steps(torch, lambda: torch.sparse.mm(A, Xd), max(3, steps // 3), 2)
+        del A
+        return ms
+    except Exception as e:  # noqa: BLE001
+        log("torch.sparse CSR SpMM not available:", repr(e)[:200])
+        return None
+
+
 def algorithmic_bytes(stats, k, normalized):
     """Bytes the method itself must move in one product: per delta one X row + its 4-byte entry
     (+ one d^-1/2 value when normalised); per row one Y write + its 4-byte marker entry (+ d^-1/2);
@@ -256,11 +279,12 @@ def report(args, torch, cbm, wl, orc, csr_ref):
     lines = ["# CBM on one MI355X: five synthetic graphs", "",
              f"`python bench.py --report <file> --steps {args.steps} --warmup {args.warmup}`; host: {os.cpu_count()} CPUs. "
              "alg. GB/s = algorithmic bytes / time (can pass the 8 TB/s HBM peak when gathers hit in L2 / Infinity Cache). "
-             "GPU CSR = the same kernels on a handle with every row stored in full. CPU columns: OpenMP CSR SpMM on all "
+             "GPU CSR = the same kernels on a handle with every row stored in full; torch.sparse CSR = the vendor library's CSR SpMM "
+             "through PyTorch on the same box (fp32 values, int64 indices), as outside context. CPU columns: OpenMP CSR SpMM on all "
              "host cores (fp32) and the numpy oracle on a row sample (1 thread).", "",
              "| graph | n | nnz(A v I) | k | deltas/nnz | depth / rounds | build s (candidate search on the host) | CBM ms | alg. GB/s | frac of HBM peak | "
-             "edges*k/s | GPU CSR ms | CBM speedup | CPU OMP CSR ms | oracle GB/s | parity err |",
-             "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
+             "edges*k/s | GPU CSR ms | CBM speedup | torch.sparse CSR ms | CPU OMP CSR ms | oracle GB/s | parity err |",
+             "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
     gcn_lines = ["", "| graph | GCN shape | CBM ms | as HIP graph replay ms | with CSR handle ms | speedup | "
                  "X.W0 ms (TFLOP/s, frac of fp32 MFMA peak) | H.W1 ms | parity err |", "|---|---|---|---|---|---|---|---|---|"]
     agg_lines = ["", "Other aggregators on the same handles (M = A v I), k as above: ms per product, CBM handle / CSR handle.", "",
@@ -282,13 +306,17 @@ def report(args, torch, cbm, wl, orc, csr_ref):
         for k in ks:
             Xh = wl.gaussian_features(g.n, k, g.meta["seed"])
             r = bench_product(torch, cbm, orc, g, h, hc, Xh, k, args.steps, args.warmup, name, d["alpha"])
+            Xd = torch.from_numpy(Xh).cuda()
+            r["vendor_csr_ms"] = vendor_csr_ms(torch, g, Xd, args.steps, args.warmup)
+            del Xd
             cpu = cpu_csr_omp_baseline(csr_ref, g, Xh, k)
             ob = cpu_oracle_baseline(orc, g, Xh, k, budget_s=5.0)
             st = r["stats"]
             nd = st["num_delta_plus"] + st["num_delta_minus"]
             lines.append(f"| {name} | {g.n} | {st['nnz']} | {k} | {nd / st['nnz']:.3f} | {st['depth']} / {st['rounds']} | {tb:.2f} ({tb_host:.2f}) | "
                          f"{r['ms']:.4f} | {r['value']:.0f} | {r['value'] / HBM_PEAK_GBS:.3f} | {r['edges_k_per_s']:.3e} | "
-                         f"{r['gpu_csr']['ms']:.4f} | {r['speedup']:.2f}x | {cpu['ms']:.2f} ({cpu['threads']} thr) | "
+                         f"{r['gpu_csr']['ms']:.4f} | {r['speedup']:.2f}x | "
+                         f"{'n/a' if r['vendor_csr_ms'] is None else format(r['vendor_csr_ms'], '.4f')} | {cpu['ms']:.2f} ({cpu['threads']} thr) | "
                          f"{ob['value']:.2f} | {r['parity_err']:.1e} |")
             results.append(dict(workload=name, k=k, **{kk: vv for kk, vv in r.items() if kk != "stats"}, stats=st,
                                 cpu_csr_omp=cpu, cpu_oracle=ob))
@@ -327,7 +355,7 @@ def report(args, torch, cbm, wl, orc, csr_ref):
             sp = cbm.cbm_stats(hp)
             lines.append(f"| collaboration, A.X x10 (no self-loops) | {g.n} | {g.nnz} | 128 | "
                          f"{(sp['num_delta_plus'] + sp['num_delta_minus']) / g.nnz:.3f} | {sp['depth']} / {sp['rounds']} | | "
-                         f"{ms10:.4f} (10 products) | | | {g.nnz * 128 * 10 / ms10 * 1e3:.3e} | | | | | |")
+                         f"{ms10:.4f} (10 products) | | | {g.nnz * 128 * 10 / ms10 * 1e3:.3e} | | | | | | |")
             cbm.cbm_free(hp)
         cbm.cbm_free(h)
         cbm.cbm_free(hc)
