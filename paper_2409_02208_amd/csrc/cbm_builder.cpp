@@ -27,6 +27,7 @@ namespace {
 constexpr int32_t kDefaultMaxDepth = 16;
 constexpr int32_t kDefaultHubCap = 512;
 constexpr int32_t kDefaultMaxCand = 8;
+constexpr int64_t kLocalityMinEntries = 32;  // mean entries per work item from which a round is scheduled by locality
 constexpr int64_t kSampleMinRows = 65536;  // automatic mode samples the compressibility of matrices this large first
 constexpr int32_t kSplitLenDefault = 512;  // most delta entries in one segment of a split row
 constexpr int32_t kSplitMinDefault = 128;  // rows with more delta entries than this are split
@@ -180,6 +181,8 @@ struct Builder {
     cbm_status validate(const int64_t* in_rowptr, const int32_t* in_colidx);
     void self_loops(const int64_t* in_rowptr, const int32_t* in_colidx);
     void transpose_matrix();
+    std::vector<int32_t> loc;  // position of every row in a breadth-first walk of the graph (square matrices)
+    void locality_order();
     std::vector<int64_t> optr;  // candidate edges bucketed by parent
     std::vector<int32_t> ochild, ow;
     bool device_candidates = false;  // run the candidate search on the GPU
@@ -258,6 +261,31 @@ void Builder::transpose_matrix() {
     rowptr = own_rowptr.data();
     colidx = own_colidx.data();
     std::swap(m, n);
+}
+
+// Breadth-first order of the rows over the graph itself (row i's columns are its neighbours): rows close in this
+// order have overlapping neighbourhoods, so their delta lists gather overlapping rows of X.
+void Builder::locality_order() {
+    loc.assign(m, -1);
+    std::vector<int32_t> queue;
+    queue.reserve(m);
+    int32_t pos = 0;
+    for (int64_t s0 = 0; s0 < m; ++s0) {
+        if (loc[s0] >= 0) continue;
+        loc[s0] = pos++;
+        queue.clear();
+        queue.push_back((int32_t)s0);
+        for (size_t qh = 0; qh < queue.size(); ++qh) {
+            const int32_t x = queue[qh];
+            for (int64_t p = rowptr[x]; p < rowptr[x + 1]; ++p) {
+                const int32_t y = colidx[p];
+                if (y < m && loc[y] < 0) {
+                    loc[y] = pos++;
+                    queue.push_back(y);
+                }
+            }
+        }
+    }
 }
 
 void Builder::all_roots() {
@@ -909,12 +937,33 @@ cbm_status Builder::emit(int32_t nrounds) {
         }
         h->seg_count[j] = (int64_t)h->tasks.size() - h->seg_begin[j];
     }
+    const bool by_locality = !loc.empty();
     for (int r = 1; r <= nrounds; ++r) {
         CbmLevel& R = h->levels[r - 1];
         auto& lt = rtasks[r];
-        std::stable_sort(lt.begin(), lt.end(), longest_first);
         R.task_begin = (int64_t)h->tasks.size();
         R.task_count = (int64_t)lt.size();
+        int64_t round_entries = 0;
+        for (auto& t : lt) round_entries += (t.len_flags & CBM_TASK_LEN_MASK);
+        // worth it for rounds of long work items (protein: 8 % faster); rounds of short ones lose more to the
+        // ragged tail of each XCD's block than they gain (and a graph without a tree has no such order at all)
+        if (by_locality && (int64_t)lt.size() >= 64 * CBM_XCD && round_entries >= kLocalityMinEntries * (int64_t)lt.size()) {
+            // neighbours in the graph next to each other, one contiguous share of the entries per XCD: what the
+            // work items running on an XCD at one time gather overlaps, and stays in that XCD's L2
+            std::stable_sort(lt.begin(), lt.end(), [&](const CbmTask& a, const CbmTask& b2) { return loc[a.row] < loc[b2.row]; });
+            const int64_t total = round_entries;
+            R.by_xcd = true;
+            size_t i = 0;
+            int64_t seen = 0;
+            for (int j = 0; j < CBM_XCD; ++j) {
+                R.xcd_begin[j] = R.task_begin + (int64_t)i;
+                const int64_t want = total * (j + 1) / CBM_XCD;
+                while (i < lt.size() && (j == CBM_XCD - 1 || seen < want)) seen += (lt[i++].len_flags & CBM_TASK_LEN_MASK);
+                R.xcd_count[j] = R.task_begin + (int64_t)i - R.xcd_begin[j];
+            }
+        } else {
+            std::stable_sort(lt.begin(), lt.end(), longest_first);
+        }
         h->tasks.insert(h->tasks.end(), lt.begin(), lt.end());
         R.comb_begin = (int64_t)h->comb.size();
         R.comb_count = (int64_t)rcomb[r].size();
@@ -1096,6 +1145,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     B.delta_lists();
     B.tree_index();
     B.plan(best_len, &nrounds);
+    if (tree && m == n && !std::getenv("CBM_NO_LOCALITY")) B.locality_order();
     cbm_stats_t& s = h->stats;
     std::memset(&s, 0, sizeof(s));
     st = B.emit(nrounds);

@@ -39,6 +39,9 @@ struct CbmLevel {
     int64_t rows_written = 0;                      // matrix rows written by the main launch
     int64_t comb_segments = 0;                     // scratch rows read by the combine launch
     int64_t comb_parent_reads = 0;
+    // work items in locality order, cut into one contiguous block per XCD (absolute indices into tasks[])
+    bool by_xcd = false;
+    int64_t xcd_begin[CBM_XCD] = {}, xcd_count[CBM_XCD] = {};
 };
 
 struct cbm_handle {

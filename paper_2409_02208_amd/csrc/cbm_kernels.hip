@@ -349,12 +349,25 @@ void launch_level(const LaunchCtx& c, const CbmLevel& L) {
     constexpr int G = 64 / LANES;
     const int ychunks = (c.k + LANES * 4 - 1) / (LANES * 4);
     CbmSegMap map{};
-    if (L.task_count > 0) {
-        dim3 grid((unsigned)((L.task_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
-        hipLaunchKernelGGL((cbm_level_kernel<RAGGED, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream,
-                           c.h->d_tasks + L.task_begin, L.task_count, map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy,
-                           c.h->d_scratch, c.ld_scratch, c.ws, c.rw, c.self_w, c.k);
+    if (L.task_count <= 0) return;
+    if (L.by_xcd) {  // one block of the (locality-ordered) work items per XCD
+        int64_t most = 0;
+        for (int j = 0; j < CBM_XCD; ++j) {
+            map.begin[j] = L.xcd_begin[j];
+            map.count[j] = L.xcd_count[j];
+            most = std::max(most, map.count[j]);
+        }
+        map.use = 1;
+        dim3 grid((unsigned)(CBM_XCD * ((most + 4 * G - 1) / (4 * G))), (unsigned)ychunks);
+        hipLaunchKernelGGL((cbm_level_kernel<RAGGED, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream, c.h->d_tasks,
+                           (int64_t)c.h->tasks.size(), map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.h->d_scratch,
+                           c.ld_scratch, c.ws, c.rw, c.self_w, c.k);
+        return;
     }
+    dim3 grid((unsigned)((L.task_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
+    hipLaunchKernelGGL((cbm_level_kernel<RAGGED, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream,
+                       c.h->d_tasks + L.task_begin, L.task_count, map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy,
+                       c.h->d_scratch, c.ld_scratch, c.ws, c.rw, c.self_w, c.k);
 }
 // all segments of all split rows, one block of work items per XCD
 template <bool RAGGED, int LANES, int MODE, int UMAX>
