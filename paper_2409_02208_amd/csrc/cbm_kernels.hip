@@ -118,8 +118,9 @@ __device__ __forceinline__ void store_row(float* row, int c0, int k, Vec4 acc, b
 // of dependent loads.  Two builds of every variant: batches of 8 rows at 4 waves per SIMD for
 // launches with few, long work items (the loads in flight come from inside each item), batches
 // of 4 at 6 or more waves per SIMD for launches with many work items (they come from occupancy).
-// Segment launches map workgroups to work items per XCD: workgroup b runs on XCD b mod 8 and takes
-// its items from that XCD's block of the task list (the segments of one column range of X).
+// Some launches map workgroups to work items per XCD: workgroup b runs on XCD b mod 8 and takes its
+// items from that XCD's block of the task list -- the segments of one column range of X, or one share
+// of a round whose work items were put in graph-locality order.
 struct CbmSegMap {
     int64_t begin[CBM_XCD];
     int64_t count[CBM_XCD];
