@@ -546,6 +546,10 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
     // of 4 spend more on that than they save (k <= 16: 25-30 % slower, measured)
     int lanes = 8;
     while (lanes < 64 && lanes * 4 < k) lanes *= 2;
+    // a feature matrix whose width is a multiple of 128 goes through in column chunks of 128, one after the other
+    // (the chunk index is the slow grid dimension): half the bytes per gathered row, so twice the rows of X stay in
+    // L2 (k = 256, 512: 5 % faster).  With a partly filled last chunk, walking the entries again costs more than that.
+    if (lanes == 64 && k % 128 == 0) lanes = 32;
     const int mode = (int)epi;
     const Variant var = aligned ? pick_lanes<false>(lanes, mode) : pick_lanes<true>(lanes, mode);
     if (h->profiling) {
