@@ -28,6 +28,7 @@ constexpr int32_t kDefaultMaxDepth = 16;
 constexpr int32_t kDefaultHubCap = 512;
 constexpr int32_t kDefaultMaxCand = 8;
 constexpr int64_t kLocalityMinEntries = 32;  // mean entries per work item from which a round is scheduled by locality
+constexpr double kLocalityEntries = 230.0;   // such a round's bandwidth grows by 1/230 of the base per entry in a work item
 constexpr int64_t kSampleMinRows = 65536;  // automatic mode samples the compressibility of matrices this large first
 constexpr int32_t kSplitLenDefault = 512;  // most delta entries in one segment of a split row
 constexpr int32_t kSplitMinDefault = 128;  // rows with more delta entries than this are split
@@ -186,6 +187,7 @@ struct Builder {
     std::vector<int64_t> optr;  // candidate edges bucketed by parent
     std::vector<int32_t> ochild, ow;
     bool device_candidates = false;  // run the candidate search on the GPU
+    bool locality = false;           // rounds of long work items will be scheduled by graph locality
     bool sample_first = false;       // estimate what a tree could save from a sample of rows before the full search
     bool skip_tree = false;          // the sample said: nothing to gain, store every row in full
     cbm_status find_candidates();
@@ -762,6 +764,7 @@ double Builder::plan(int64_t path_max, int32_t* nrounds_out) {
     *nrounds_out = nrounds;
     // cost: per round, entries gathered and the longest path; split rows add one segment launch and combines
     std::vector<int64_t> entries(nrounds + 1, 0), rows(nrounds + 1, 0), longest(nrounds + 1, 0), comb(nrounds + 1, 0);
+    std::vector<int64_t> heads(nrounds + 1, 0), written(nrounds + 1, 0);
     int64_t seg_entries = 0;
     bool fixup = false;
     for (int64_t i = 0; i < m; ++i) {
@@ -775,20 +778,35 @@ double Builder::plan(int64_t path_max, int32_t* nrounds_out) {
             continue;
         }
         entries[r] += dlen(x);
-        rows[r] += 1 + (h->parent[x] >= 0 && next[h->parent[x]] != x);  // Y write (+ parent read for a head)
+        const bool head = h->parent[x] < 0 || next[h->parent[x]] != x;
+        rows[r] += 1 + (h->parent[x] >= 0 && head);  // Y write (+ parent read for a head)
+        heads[r] += head;
+        ++written[r];
         if (next[x] < 0) longest[r] = std::max(longest[r], run[x]);
     }
     double us = 0.0;
     if (seg_entries > 0)
         us += kLaunchUs + std::max((double)split_len * kEntryUs, seg_entries * kRefRowBytes / (2.0 * kBytesPerUs));
     for (int r = 1; r <= nrounds; ++r) {
-        double round_us = 0.0;
-        if (entries[r] + rows[r] > 0)
-            round_us += kLaunchUs + std::max(longest[r] * kEntryUs, (entries[r] + rows[r]) * kRefRowBytes / kBytesPerUs);
-        if (comb[r] > 0) round_us += kLaunchUs + comb[r] * kRefRowBytes / kBytesPerUs;
+        double round_us = 0.0, bytes_us = 0.0;
+        if (entries[r] + rows[r] > 0) {
+            // a round of long work items is scheduled by graph locality (see emit): more of its gathers hit in L2
+            const bool local = locality && heads[r] >= 64 * CBM_XCD && entries[r] + written[r] >= kLocalityMinEntries * heads[r];
+            // measured on the protein recipe: 1.25x the base rate at 68 entries per work item, 1.6x at 130, 2.4x at 320
+            const double per_item = heads[r] > 0 ? (double)(entries[r] + written[r]) / (double)heads[r] : 0.0;
+            // ... and less when there are too few long items to fill the chip (2,500 of them: 0.6 of the rate of 12,000)
+            const double fill = (double)heads[r] / ((double)heads[r] + 2048.0);
+            const double rate = local ? kBytesPerUs * (1.0 + std::min(1.5, per_item / kLocalityEntries)) * fill / 0.85 : kBytesPerUs;
+            bytes_us = (entries[r] + rows[r]) * kRefRowBytes / rate;
+            round_us += kLaunchUs + std::max(longest[r] * kEntryUs, bytes_us);
+        }
+        if (comb[r] > 0) {
+            round_us += kLaunchUs + comb[r] * kRefRowBytes / kBytesPerUs;
+            bytes_us += comb[r] * kRefRowBytes / kBytesPerUs;
+        }
         us += round_us;
         last_round_us = round_us;
-        last_round_bytes_us = (entries[r] + rows[r] + comb[r]) * kRefRowBytes / kBytesPerUs;
+        last_round_bytes_us = bytes_us;
     }
     if (fixup && h->square_self_loops) us += kLaunchUs;
     return us;
@@ -1047,6 +1065,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     std::vector<int64_t> split_choices = {kSplitMinDefault, kSplitLenDefault};
     if (std::getenv("CBM_SPLIT_MIN")) split_choices = {B.split_min};
     bool tree = B.max_depth != 1 && m > 1;
+    B.locality = m == n && !std::getenv("CBM_NO_LOCALITY");
     const bool exact_tree = (o.flags & CBM_FLAG_EXACT_TREE) != 0;
     if (o.flags & CBM_FLAG_DEVICE_BUILD) {
         if ((o.flags & CBM_FLAG_HOST_ONLY) || B.max_cand < 1 || B.max_cand > 16) return CBM_ERR_INVALID_ARG;
@@ -1145,7 +1164,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     B.delta_lists();
     B.tree_index();
     B.plan(best_len, &nrounds);
-    if (tree && m == n && !std::getenv("CBM_NO_LOCALITY")) B.locality_order();
+    if (tree && B.locality) B.locality_order();
     cbm_stats_t& s = h->stats;
     std::memset(&s, 0, sizeof(s));
     st = B.emit(nrounds);
