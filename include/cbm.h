@@ -164,7 +164,11 @@ cbm_status cbm_build(int64_t m, int64_t n, const int64_t* rowptr, const int32_t*
  * byte on a large graph, so pad the feature dimension to a multiple of 4 where
  * speed matters.
  * Not thread-safe per handle (rows with very long delta lists use scratch owned
- * by the handle, sized on first use for a given k).
+ * by the handle, sized on first use for a given k).  That first use allocates:
+ * call the product once with the widest k before capturing it in a HIP graph;
+ * later calls with the same or a smaller k only launch kernels and can be
+ * captured.  Per-launch profiling (cbm_profile_enable) records events and must
+ * be off during capture.
  */
 cbm_status cbm_spmm(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
                     void* hip_stream);
