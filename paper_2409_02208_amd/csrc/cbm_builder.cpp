@@ -884,62 +884,95 @@ cbm_status Builder::emit(int32_t nrounds) {
     h->tasks.clear();
     h->comb.clear();
     h->stream.clear();
-    h->stream.reserve((size_t)(h->dptr[m] + m));
     h->num_slots = 0;
     h->seg_deltas = 0;
     int64_t split_rows = 0;
     std::vector<std::vector<CbmTask>> rtasks(nrounds + 1), rcomb(nrounds + 1);
     std::vector<std::vector<CbmTask>> seg_tasks((size_t)CBM_XCD * (phases + 1));  // [xcd][phase]; last = unphased
+    // Pass 1, in order: where every work item's entries go in the stream (heads of paths and split rows only).
+    struct Piece {
+        int32_t x;
+        int64_t base;  // first entry in the stream
+    };
+    std::vector<Piece> paths, splits;
+    int64_t at = 0;
     for (int64_t i = 0; i < m; ++i) {
         const int32_t x = order[i];
         const int32_t y = h->parent[x];
         if (y >= 0 && next[y] == x) continue;  // not a head
         CbmLevel& R = h->levels[round[x] - 1];
         if (is_split(x)) {
-            // A long row is cut into segments that depend on nothing.  Its entries are re-sorted by column
-            // and cut at the CBM_XCD column-range boundaries first: all segments of one column range run on
-            // one XCD (workgroup id mod 8), so the popular rows of X in that range stay in that XCD's L2.
-            // Very long rows are cut finer still: each XCD's range is walked in `phases` sub-ranges, one after
-            // the other, so that at any time an XCD gathers from 1/(8 phases) of X.
-            ++split_rows;
-            const int64_t len = dlen(x);
-            const int64_t base = (int64_t)h->stream.size();
-            h->stream.insert(h->stream.end(), h->dcol.begin() + h->dptr[x], h->dcol.begin() + h->dptr[x + 1]);
-            std::sort(h->stream.begin() + base, h->stream.end(), [](uint32_t a, uint32_t b2) {
-                return (a & CBM_ENTRY_INDEX_MASK) < (b2 & CBM_ENTRY_INDEX_MASK);
-            });
-            const int64_t slot0 = h->num_slots;
-            const int fine = len >= fine_min ? phases : 1;  // pieces per XCD range
-            const int npieces = CBM_XCD * fine;
-            int64_t pos = 0;
-            for (int f = 0; f < npieces; ++f) {
-                const uint32_t hi = (uint32_t)(((int64_t)(f + 1) * n + npieces - 1) / npieces);  // columns < hi
-                int64_t end = pos;
-                while (end < len && (h->stream[base + end] & CBM_ENTRY_INDEX_MASK) < hi) ++end;
-                auto& list = seg_tasks[(size_t)(f / fine) * (phases + 1) + (fine > 1 ? f % fine : phases)];
-                for (int64_t b = pos; b < end; b += split_len) {
-                    const int64_t e = std::min(end, b + split_len);
-                    list.push_back({(int32_t)h->num_slots, -1, (uint32_t)(base + b), (uint32_t)(e - b) | CBM_TASK_SEGMENT});
-                    ++h->num_slots;
-                }
-                pos = end;
-            }
-            const int64_t nseg = h->num_slots - slot0;
-            h->seg_deltas += len;
-            rcomb[round[x]].push_back({x, y, (uint32_t)slot0, (uint32_t)nseg | (internal[x] ? CBM_TASK_INTERNAL : 0u)});
-            R.comb_segments += nseg;
-            R.comb_parent_reads += y >= 0;
+            splits.push_back({x, at});
+            at += dlen(x);
             continue;
         }
-        const int64_t start = (int64_t)h->stream.size();
+        const int64_t start = at;
         for (int32_t v = x; v >= 0; v = next[v]) {
-            h->stream.insert(h->stream.end(), h->dcol.begin() + h->dptr[v], h->dcol.begin() + h->dptr[v + 1]);
-            h->stream.push_back((uint32_t)v | CBM_ENTRY_MARK | (internal[v] ? CBM_ENTRY_INTERNAL : 0u));
+            at += dlen(v) + 1;
             R.deltas += dlen(v);
             ++R.rows_written;
         }
-        rtasks[round[x]].push_back({x, y, (uint32_t)start, (uint32_t)((int64_t)h->stream.size() - start)});
+        paths.push_back({x, start});
+        rtasks[round[x]].push_back({x, y, (uint32_t)start, (uint32_t)(at - start)});
         R.parent_reads += y >= 0;
+    }
+    if (at >= (int64_t)UINT32_MAX) return CBM_ERR_UNSUPPORTED;
+    h->stream.resize((size_t)at);
+    // Pass 2, on all threads: the entries themselves.  A path is its rows' deltas, each followed by the row's marker;
+    // a split row is its deltas re-sorted by column.
+    parallel_chunks(nthreads, (int64_t)paths.size(), 256, [&](int64_t b, int64_t e, int) {
+        for (int64_t i = b; i < e; ++i) {
+            uint32_t* out = h->stream.data() + paths[i].base;
+            for (int32_t v = paths[i].x; v >= 0; v = next[v]) {
+                out = std::copy(h->dcol.begin() + h->dptr[v], h->dcol.begin() + h->dptr[v + 1], out);
+                *out++ = (uint32_t)v | CBM_ENTRY_MARK | (internal[v] ? CBM_ENTRY_INTERNAL : 0u);
+            }
+        }
+    });
+    parallel_chunks(nthreads, (int64_t)splits.size(), 4, [&](int64_t b, int64_t e, int) {
+        for (int64_t i = b; i < e; ++i) {
+            const int32_t x = splits[i].x;
+            uint32_t* out = h->stream.data() + splits[i].base;
+            std::copy(h->dcol.begin() + h->dptr[x], h->dcol.begin() + h->dptr[x + 1], out);
+            if (h->nminus[x] > 0)  // Delta+ alone is already in column order
+                std::sort(out, out + dlen(x), [](uint32_t a, uint32_t b2) {
+                    return (a & CBM_ENTRY_INDEX_MASK) < (b2 & CBM_ENTRY_INDEX_MASK);
+                });
+        }
+    });
+    // Pass 3, in order: a long row is cut into segments that depend on nothing.  Its entries, sorted by column,
+    // are cut at the CBM_XCD column-range boundaries first: all segments of one column range run on one XCD
+    // (workgroup id mod 8), so the popular rows of X in that range stay in that XCD's L2.  Very long rows are cut
+    // finer still: each XCD's range is walked in `phases` sub-ranges, one after the other, so that at any time an
+    // XCD gathers from 1/(8 phases) of X.
+    for (const Piece& sp : splits) {
+        const int32_t x = sp.x;
+        const int32_t y = h->parent[x];
+        CbmLevel& R = h->levels[round[x] - 1];
+        ++split_rows;
+        const int64_t len = dlen(x);
+        const int64_t base = sp.base;
+        const uint32_t* ent = h->stream.data() + base;
+        const int64_t slot0 = h->num_slots;
+        const int fine = len >= fine_min ? phases : 1;  // pieces per XCD range
+        const int npieces = CBM_XCD * fine;
+        int64_t pos = 0;
+        for (int f = 0; f < npieces; ++f) {
+            const uint32_t hi = (uint32_t)(((int64_t)(f + 1) * n + npieces - 1) / npieces);  // columns < hi
+            const int64_t end = std::partition_point(ent + pos, ent + len, [&](uint32_t e2) { return (e2 & CBM_ENTRY_INDEX_MASK) < hi; }) - ent;
+            auto& list = seg_tasks[(size_t)(f / fine) * (phases + 1) + (fine > 1 ? f % fine : phases)];
+            for (int64_t b = pos; b < end; b += split_len) {
+                const int64_t e = std::min(end, b + split_len);
+                list.push_back({(int32_t)h->num_slots, -1, (uint32_t)(base + b), (uint32_t)(e - b) | CBM_TASK_SEGMENT});
+                ++h->num_slots;
+            }
+            pos = end;
+        }
+        const int64_t nseg = h->num_slots - slot0;
+        h->seg_deltas += len;
+        rcomb[round[x]].push_back({x, y, (uint32_t)slot0, (uint32_t)nseg | (internal[x] ? CBM_TASK_INTERNAL : 0u)});
+        R.comb_segments += nseg;
+        R.comb_parent_reads += y >= 0;
     }
     if ((int64_t)h->stream.size() >= (int64_t)UINT32_MAX) return CBM_ERR_UNSUPPORTED;
     // longest first: wave-mates get similar lengths and the tail of a launch is short
