@@ -21,6 +21,10 @@
 
 namespace {
 
+constexpr int kHashBits = 13;
+constexpr int kHashSlots = 1 << kHashBits;           // counters a workgroup keeps in LDS (keys + counts: 64 KiB)
+constexpr unsigned kHashLimit = kHashSlots - 1024;  // distinct rows from which the table is given up: up to 256 lanes x 4
+                                                     // insertions may still land after that, and it must never fill
 constexpr int kCandMax = 16;          // most candidates kept per row
 constexpr int kSelMax = 2 * kCandMax;  // most candidates settled by exact intersection
 
@@ -31,6 +35,9 @@ struct CandArgs {
     const int64_t* tptr;  // its transpose: rows holding each column
     const int32_t* trow;
     const int32_t* order;  // rows in the order workgroups take them (heaviest first)
+    int64_t nheavy;        // the first nheavy of them expand to too many rows for an LDS table: dense counters at once
+    int32_t* overflow;     // [m] rows whose LDS table filled up: left to the dense pass
+    unsigned long long* noverflow;
     int64_t hub_cap;       // columns held by more rows than this are not expanded (< 0: no cap)
     int64_t min_saving;    // a candidate must save at least this many deltas
     int32_t keep;          // candidates kept per row, <= kCandMax
@@ -69,9 +76,17 @@ __device__ __forceinline__ int64_t wave_sum(int64_t v) {
     return v;
 }
 
+// Shared-column counters of one row.  Most rows touch a few thousand others at most: the TABLE pass counts those in
+// an LDS hash table (open addressing; a key is claimed with compare-and-swap, then its count is bumped) and puts a row
+// that touches more on a list.  The dense pass (TABLE = false, no LDS, more workgroups per CU) then takes the heavy
+// rows and that list, counting in the workgroup's dense array of m counters in device memory.
+template <bool TABLE>
 __global__ __launch_bounds__(256) void cbm_candidates_kernel(const CandArgs a) {
+    extern __shared__ int s_table[];  // kHashSlots keys (-1 = free), then kHashSlots counts
+    int* s_key = s_table;
+    unsigned* s_cnt = reinterpret_cast<unsigned*>(s_table + kHashSlots);
     __shared__ unsigned long long s_row;
-    __shared__ unsigned s_ntouched, s_npass, s_nhub;
+    __shared__ unsigned s_ntouched, s_npass, s_nhub, s_distinct, s_overflow;
     __shared__ unsigned long long s_sel[kSelMax];
     __shared__ long long s_saving[kSelMax];
     __shared__ unsigned long long s_red[4];
@@ -79,6 +94,13 @@ __global__ __launch_bounds__(256) void cbm_candidates_kernel(const CandArgs a) {
     int32_t* touched = a.touched + (size_t)blockIdx.x * a.m;
     unsigned long long* pass = a.pass + (size_t)blockIdx.x * a.m;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (TABLE)
+        for (int i = tid; i < kHashSlots; i += 256) {
+            s_key[i] = -1;
+            s_cnt[i] = 0;
+        }
+    // work list: TABLE: order[nheavy..m); dense: order[0..nheavy), then the rows the table pass gave up on
+    const unsigned long long nwork = TABLE ? (unsigned long long)(a.m - a.nheavy) : (unsigned long long)a.nheavy + *a.noverflow;
 
     for (;;) {
         __syncthreads();  // everyone is done with the shared state of the previous row
@@ -87,48 +109,107 @@ __global__ __launch_bounds__(256) void cbm_candidates_kernel(const CandArgs a) {
             s_ntouched = 0;
             s_npass = 0;
             s_nhub = 0;
+            s_distinct = 0;
+            s_overflow = 0;
         }
         __syncthreads();
-        if (s_row >= (unsigned long long)a.m) return;  // the queue only grows: every workgroup gets here
-        const int32_t x = a.order[s_row];
+        if (s_row >= nwork) return;  // the queue only grows: every workgroup gets here
+        const int32_t x = TABLE ? a.order[a.nheavy + s_row]
+                                : s_row < (unsigned long long)a.nheavy ? a.order[s_row] : a.overflow[s_row - a.nheavy];
         const int64_t xb = a.rowptr[x], nx = a.rowptr[x + 1] - xb;
         if (nx < 1) {
             if (tid == 0) a.out_n[x] = 0;
             continue;
         }
-
-        // 1. count shared columns: a column per group of 16 lanes, the column's rows over the lanes
         const int grp = tid >> 4, gl = tid & 15;
-        unsigned myhub = 0;
-        for (int64_t p = grp; p < nx; p += 16) {
-            const int32_t j = a.colidx[xb + p];
-            const int64_t tb = a.tptr[j], deg = a.tptr[j + 1] - tb;
-            if (a.hub_cap >= 0 && deg > a.hub_cap) {  // a hub column: too many rows to expand
-                if (gl == 0) ++myhub;
+        constexpr bool in_lds = TABLE;
+
+        // 1a. count shared columns in the LDS table: a column per group of 16 lanes, the column's rows over the lanes
+        if (in_lds) {
+            unsigned myhub = 0;
+            volatile unsigned* overflow = &s_overflow;  // set by any lane, read by all: never kept in a register
+            for (int64_t p = grp; p < nx && !*overflow; p += 16) {
+                const int32_t j = a.colidx[xb + p];
+                const int64_t tb = a.tptr[j], deg = a.tptr[j + 1] - tb;
+                if (a.hub_cap >= 0 && deg > a.hub_cap) {
+                    if (gl == 0) ++myhub;
+                    continue;
+                }
+                for (int64_t q = gl; q < deg && !*overflow; q += 16) {
+                    const int32_t y = a.trow[tb + q];
+                    unsigned slot = ((unsigned)y * 2654435761u) >> (32 - kHashBits);
+                    // The table always keeps free slots (kHashLimit), so a probe sequence meets one; the bound on
+                    // the walk makes the loop end whatever happens, and a row that hits it is counted again densely.
+                    int probe = 0;
+                    for (; probe < kHashSlots; ++probe) {
+                        int key = *(volatile int*)&s_key[slot];
+                        if (key == -1) key = atomicCAS(&s_key[slot], -1, y);
+                        if (key == -1 || key == y) {
+                            atomicAdd(&s_cnt[slot], 1u);
+                            if (key == -1 && atomicAdd(&s_distinct, 1u) >= kHashLimit) *overflow = 1;
+                            break;
+                        }
+                        slot = (slot + 1) & (kHashSlots - 1);
+                    }
+                    if (probe == kHashSlots) *overflow = 1;
+                }
+            }
+            if (myhub) atomicAdd(&s_nhub, myhub);
+            __syncthreads();
+            if (*overflow) {  // too many distinct rows: empty the table and leave this row to the dense pass
+                for (int i = tid; i < kHashSlots; i += 256) {
+                    s_key[i] = -1;
+                    s_cnt[i] = 0;
+                }
+                if (tid == 0) a.overflow[atomicAdd(a.noverflow, 1ull)] = x;
                 continue;
             }
-            for (int64_t q = gl; q < deg; q += 64) {  // four counters in flight per lane
-                int32_t y[4];
-                uint32_t old[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) y[u] = q + 16 * u < deg ? a.trow[tb + q + 16 * u] : -1;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) old[u] = y[u] >= 0 ? atomicAdd(&cnt[y[u]], 1u) : 1u;
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (old[u] == 0u) touched[atomicAdd(&s_ntouched, 1u)] = y[u];
-            }
         }
-        if (myhub) atomicAdd(&s_nhub, myhub);
-        __syncthreads();
-        const unsigned ntouched = s_ntouched;
+
+        // 1b. ... or in the dense array
+        if (!in_lds) {
+            unsigned myhub = 0;
+            for (int64_t p = grp; p < nx; p += 16) {
+                const int32_t j = a.colidx[xb + p];
+                const int64_t tb = a.tptr[j], deg = a.tptr[j + 1] - tb;
+                if (a.hub_cap >= 0 && deg > a.hub_cap) {  // a hub column: too many rows to expand
+                    if (gl == 0) ++myhub;
+                    continue;
+                }
+                for (int64_t q = gl; q < deg; q += 64) {  // four counters in flight per lane
+                    int32_t y[4];
+                    uint32_t old[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) y[u] = q + 16 * u < deg ? a.trow[tb + q + 16 * u] : -1;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) old[u] = y[u] >= 0 ? atomicAdd(&cnt[y[u]], 1u) : 1u;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (old[u] == 0u) touched[atomicAdd(&s_ntouched, 1u)] = y[u];
+                }
+            }
+            if (myhub) atomicAdd(&s_nhub, myhub);
+            __syncthreads();
+        }
+        const unsigned ntouched = in_lds ? (unsigned)kHashSlots : s_ntouched;
         const int64_t nhub = s_nhub;
 
-        // 2. score what was touched (upper bound of the saving where hub columns were skipped); the exchange
-        //    reads the counter where the atomics counted it and leaves it zero for the next row
+        // 2. score what was touched (upper bound of the saving where hub columns were skipped) and leave every counter
+        //    zero for the next row: table slots are read and freed; a dense counter is read and cleared by one
+        //    exchange, where the atomics counted it
         for (unsigned i = tid; i < ntouched; i += 256) {
-            const int32_t y = touched[i];
-            const int64_t shared = (int64_t)atomicExch(&cnt[y], 0u);
+            int32_t y;
+            int64_t shared;
+            if (in_lds) {
+                y = s_key[i];
+                if (y == -1) continue;
+                shared = (int64_t)s_cnt[i];
+                s_key[i] = -1;
+                s_cnt[i] = 0;
+            } else {
+                y = touched[i];
+                shared = (int64_t)atomicExch(&cnt[y], 0u);
+            }
             if (y == x) continue;
             const int64_t ny = a.rowptr[y + 1] - a.rowptr[y];
             const int64_t room = (ny < nx ? ny : nx) - shared;  // columns the two rows could still share among the hubs
@@ -288,6 +369,7 @@ cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t
 
     // heaviest rows first: the expansion of row x touches sum over its non-hub columns of the column's rows
     std::vector<int32_t> order(m);
+    int64_t nheavy = 0;
     {
         std::vector<int64_t> work(m);
         const int nt = (int)std::max(1u, std::min(32u, std::thread::hardware_concurrency()));
@@ -304,14 +386,45 @@ cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t
                 }
             });
         for (auto& th : pool) th.join();
+        // Which rows go straight to the dense counters?  A row whose expansion is shorter than the table is safe in the
+        // table.  In between it depends on the graph: where neighbourhoods overlap (the expansion of a row of a
+        // nearest-neighbour graph revisits the same few thousand rows) the table holds rows that expand to a quarter of
+        // a million; where they do not (power-law graphs) such rows overflow it.  Count the distinct rows of a few.
+        int64_t heavy_from = 1 << 18;
+        {
+            std::vector<int32_t> mid;
+            for (int64_t x = 0; x < m; ++x)
+                if (work[x] >= (int64_t)kHashLimit && work[x] < heavy_from) mid.push_back((int32_t)x);
+            const size_t nsample = std::min<size_t>(48, mid.size());
+            size_t spilled = 0;
+            std::vector<uint8_t> seen(nsample ? m : 0, 0);
+            std::vector<int32_t> hit;
+            for (size_t i = 0; i < nsample; ++i) {
+                const int32_t x = mid[i * mid.size() / nsample];
+                hit.clear();
+                for (int64_t p = rowptr[x]; p < rowptr[x + 1]; ++p) {
+                    const int32_t j = colidx[p];
+                    if (hub_cap >= 0 && tptr[j + 1] - tptr[j] > hub_cap) continue;
+                    for (int64_t q = tptr[j]; q < tptr[j + 1]; ++q)
+                        if (!seen[trow[q]]) {
+                            seen[trow[q]] = 1;
+                            hit.push_back(trow[q]);
+                        }
+                }
+                spilled += hit.size() > kHashLimit;
+                for (int32_t y : hit) seen[y] = 0;
+            }
+            if (nsample > 0 && 2 * spilled >= nsample) heavy_from = kHashLimit;
+        }
         std::vector<std::pair<int64_t, int32_t>> heavy;
         size_t w = 0;
         for (int64_t x = 0; x < m; ++x)
-            if (work[x] >= (1 << 18)) heavy.push_back({work[x], (int32_t)x});
+            if (work[x] >= heavy_from) heavy.push_back({work[x], (int32_t)x});
         std::sort(heavy.begin(), heavy.end(), [](const auto& p, const auto& q) { return p.first > q.first; });
+        nheavy = (int64_t)heavy.size();
         for (auto& p : heavy) order[w++] = p.second;
         for (int64_t x = 0; x < m; ++x)
-            if (work[x] < (1 << 18)) order[w++] = (int32_t)x;
+            if (work[x] < heavy_from) order[w++] = (int32_t)x;
     }
     lap("row order");
     // one counter array, one touched list and one key list of m entries per workgroup
@@ -338,7 +451,8 @@ cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t
     CAND_TRY(buf.alloc(&d_tptr, n + 1), CBM_ERR_ALLOC);
     CAND_TRY(buf.alloc(&d_trow, nnz), CBM_ERR_ALLOC);
     CAND_TRY(buf.alloc(&d_order, m), CBM_ERR_ALLOC);
-    CAND_TRY(buf.alloc(&a.next, 1), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&a.next, 2), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&a.overflow, m), CBM_ERR_ALLOC);
     CAND_TRY(buf.alloc(&a.cnt, (size_t)nwg * m), CBM_ERR_ALLOC);
     CAND_TRY(buf.alloc(&a.touched, (size_t)nwg * m), CBM_ERR_ALLOC);
     CAND_TRY(buf.alloc(&a.pass, (size_t)nwg * m), CBM_ERR_ALLOC);
@@ -352,7 +466,8 @@ cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t
     }
     CAND_TRY(hipMemcpy(d_tptr, tptr, (size_t)(n + 1) * 8, hipMemcpyHostToDevice), CBM_ERR_HIP);
     CAND_TRY(hipMemcpy(d_order, order.data(), (size_t)m * 4, hipMemcpyHostToDevice), CBM_ERR_HIP);
-    CAND_TRY(hipMemset(a.next, 0, sizeof(unsigned long long)), CBM_ERR_HIP);
+    CAND_TRY(hipMemset(a.next, 0, 2 * sizeof(unsigned long long)), CBM_ERR_HIP);
+    a.noverflow = a.next + 1;
     CAND_TRY(hipMemset(a.cnt, 0, (size_t)nwg * m * sizeof(uint32_t)), CBM_ERR_HIP);
     CAND_TRY(hipDeviceSynchronize(), CBM_ERR_HIP);
     lap("alloc + upload");
@@ -362,13 +477,27 @@ cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t
     a.tptr = d_tptr;
     a.trow = d_trow;
     a.order = d_order;
+    a.nheavy = nheavy;
     a.hub_cap = hub_cap;
     a.min_saving = min_saving;
     a.keep = keep;
-    hipLaunchKernelGGL(cbm_candidates_kernel, dim3((unsigned)nwg), dim3(256), 0, 0, a);
+    const size_t lds = (size_t)kHashSlots * 8;
+    CAND_TRY(hipFuncSetAttribute((const void*)cbm_candidates_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
+             CBM_ERR_HIP);
+    hipLaunchKernelGGL(cbm_candidates_kernel<true>, dim3((unsigned)nwg), dim3(256), lds, 0, a);
+    CAND_TRY(hipGetLastError(), CBM_ERR_HIP);
+    if (verbose) {
+        CAND_TRY(hipDeviceSynchronize(), CBM_ERR_HIP);
+        unsigned long long nov = 0;
+        CAND_TRY(hipMemcpy(&nov, a.noverflow, sizeof(nov), hipMemcpyDeviceToHost), CBM_ERR_HIP);
+        std::fprintf(stderr, "[cbm_build]   device candidates: %ld heavy rows, %llu rows left by the table pass\n", (long)nheavy, nov);
+        lap("table pass");
+    }
+    CAND_TRY(hipMemsetAsync(a.next, 0, sizeof(unsigned long long), 0), CBM_ERR_HIP);  // the dense pass has its own queue
+    hipLaunchKernelGGL(cbm_candidates_kernel<false>, dim3((unsigned)nwg), dim3(256), 0, 0, a);
     CAND_TRY(hipGetLastError(), CBM_ERR_HIP);
     CAND_TRY(hipDeviceSynchronize(), CBM_ERR_HIP);
-    lap("kernel");
+    lap("dense pass");
     CAND_TRY(hipMemcpy(out_n->data(), a.out_n, (size_t)m * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
     CAND_TRY(hipMemcpy(out_y->data(), a.out_y, (size_t)m * keep * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
     CAND_TRY(hipMemcpy(out_w->data(), a.out_w, (size_t)m * keep * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
