@@ -3,11 +3,12 @@
 // The compression tree is chosen among "candidate" edges (y, x): rows y that share columns with
 // row x, ranked by the Hamming distance of Lemma 2.1, w(y,x) = nnz(a_x) + nnz(a_y) - 2 |a_x n a_y|.
 // Finding them is the pattern of the sparse product A A^T: for every column j of row x, every row y
-// of column j shares one more column with x.  One workgroup owns one row at a time and counts in a
-// dense array of its own (one counter per row of the matrix: the chip's memory is large enough to give
-// every resident workgroup such an array), then scores the rows it touched, keeps the best few and
-// settles them by exact list intersection where columns were skipped as hubs.  The selection rule and
-// the tie-breaks are those of the host search, so both produce the same candidate set.
+// of column j shares one more column with x.  One workgroup owns one row at a time and counts either
+// in an LDS hash table (rows that meet a few thousand others at most) or in a dense array of its own
+// (one counter per row of the matrix: the chip's memory is large enough to give every resident
+// workgroup such an array), then scores the rows it met, keeps the best few and settles them by exact
+// list intersection where columns were skipped as hubs.  The selection rule and the tie-breaks are
+// those of the host search, so both produce the same candidate set.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
