@@ -191,7 +191,10 @@ struct Builder {
     bool sample_first = false;       // estimate what a tree could save from a sample of rows before the full search
     bool skip_tree = false;          // the sample said: nothing to gain, store every row in full
     cbm_status find_candidates();
+    std::vector<int32_t> kept_parent, kept_level;  // the best of the grown trees while "no tree" is being priced
+    std::vector<int64_t> kept_dptr;
     void prim(int64_t seeds);
+    void prim(int64_t seeds, std::vector<int32_t>& parent, std::vector<int32_t>& level, std::vector<int64_t>& dptr) const;
     void arborescence();
     void all_roots();
     void delta_lists();
@@ -450,9 +453,12 @@ cbm_status Builder::find_candidates() {
 // with a depth cap, growing from many seeds at once gives wider levels (more parallel work per
 // dependent launch) and often fewer deltas than growing from the few cheapest rows only.
 // Also leaves in dptr[] the delta count of every row (the weight of its tree edge).
-void Builder::prim(int64_t seeds) {
-    h->parent.assign(m, -1);
-    h->level.assign(m, 0);
+void Builder::prim(int64_t seeds) { prim(seeds, h->parent, h->level, h->dptr); }
+
+// The same into arrays of the caller's (reads the builder only: several growths can run side by side).
+void Builder::prim(int64_t seeds, std::vector<int32_t>& parent, std::vector<int32_t>& level, std::vector<int64_t>& dptr) const {
+    parent.assign(m, -1);
+    level.assign(m, 0);
     std::vector<int32_t> wsel(m, 0);
     std::vector<HeapEdge> init;
     init.reserve(m);
@@ -464,17 +470,17 @@ void Builder::prim(int64_t seeds) {
     while (!pq.empty()) {
         HeapEdge e = pq.top();
         pq.pop();
-        if (h->level[e.x] != 0) continue;
-        int32_t lvl = e.y < 0 ? 1 : h->level[e.y] + 1;
-        h->parent[e.x] = e.y;
-        h->level[e.x] = lvl;
+        if (level[e.x] != 0) continue;
+        int32_t lvl = e.y < 0 ? 1 : level[e.y] + 1;
+        parent[e.x] = e.y;
+        level[e.x] = lvl;
         wsel[e.x] = e.y < 0 ? (int32_t)rlen(e.x) : (int32_t)(e.key >> 1);
         if (max_depth > 0 && lvl >= max_depth) continue;  // nothing may hang below the cap
         for (int64_t p = optr[e.x]; p < optr[e.x + 1]; ++p)
-            if (h->level[ochild[p]] == 0) pq.push({((uint64_t)ow[p] << 1) | 1u, ochild[p], e.x});
+            if (level[ochild[p]] == 0) pq.push({((uint64_t)ow[p] << 1) | 1u, ochild[p], e.x});
     }
-    h->dptr.assign(m + 1, 0);
-    for (int64_t x = 0; x < m; ++x) h->dptr[x + 1] = h->dptr[x] + wsel[x];
+    dptr.assign(m + 1, 0);
+    for (int64_t x = 0; x < m; ++x) dptr[x + 1] = dptr[x] + wsel[x];
 }
 
 // Exact minimum-cost arborescence of the candidate digraph rooted at the virtual vertex (Section 2.2,
@@ -1092,7 +1098,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     // model may also find that no tree pays for its extra launches (small graphs): then every row is
     // stored in full.  A depth cap of 1 means exactly that and needs no candidate search.
     int32_t nrounds = 0;
-    int64_t best_len = kPathChoices[0], best_seeds = 0, best_split = B.split_min;
+    int64_t best_len = kPathChoices[0], best_split = B.split_min;
     // rows longer than the split threshold are cut into per-XCD segments: worth a launch or two of their own on
     // graphs with many long rows, a loss where only a handful exist
     std::vector<int64_t> split_choices = {kSplitMinDefault, kSplitLenDefault};
@@ -1127,9 +1133,32 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
         const int64_t forced_len = env_or("CBM_PATH_MAX", 0);
         const int64_t forced_seeds = o.seed_roots > 0 ? o.seed_roots : o.seed_roots < 0 ? 0 : env_or("CBM_SEED_ROOTS", -1);
         double best_us = 1e300;
+        // the trees grown from 0, m/128, m/32, m/8 seeded roots, side by side (or the one the caller asked for)
+        struct Grown {
+            int64_t seeds;
+            std::vector<int32_t> parent, level;
+            std::vector<int64_t> dptr;
+        };
+        std::vector<Grown> grown;
         for (int64_t seeds : {(int64_t)0, m / 128, m / 32, m / 8}) {
-            if (forced_seeds >= 0) seeds = forced_seeds;
-            B.prim(seeds);
+            grown.push_back({forced_seeds >= 0 ? forced_seeds : seeds, {}, {}, {}});
+            if (forced_seeds >= 0 || m < 1024) break;
+        }
+        {
+            std::vector<std::thread> pool;
+            for (size_t i = 1; i < grown.size() && B.nthreads > 1; ++i)
+                pool.emplace_back([&, i] { B.prim(grown[i].seeds, grown[i].parent, grown[i].level, grown[i].dptr); });
+            B.prim(grown[0].seeds, grown[0].parent, grown[0].level, grown[0].dptr);
+            for (auto& th : pool) th.join();
+            for (size_t i = 1; i < grown.size() && B.nthreads <= 1; ++i)
+                B.prim(grown[i].seeds, grown[i].parent, grown[i].level, grown[i].dptr);
+        }
+        size_t best_tree = 0;
+        for (size_t gi = 0; gi < grown.size(); ++gi) {
+            const int64_t seeds = grown[gi].seeds;
+            h->parent.swap(grown[gi].parent);
+            h->level.swap(grown[gi].level);
+            h->dptr.swap(grown[gi].dptr);
             for (int64_t split : split_choices) {
                 B.split_min = split;
                 B.tree_index();
@@ -1144,14 +1173,20 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
                     if (us < best_us) {
                         best_us = us;
                         best_len = cap;
-                        best_seeds = seeds;
                         best_split = split;
+                        best_tree = gi;
                     }
                     if (forced_len > 0) break;
                 }
             }
-            if (forced_seeds >= 0 || m < 1024) break;
+            h->parent.swap(grown[gi].parent);
+            h->level.swap(grown[gi].level);
+            h->dptr.swap(grown[gi].dptr);
         }
+        B.kept_parent.swap(grown[best_tree].parent);  // the winner, for after the comparison with "no tree"
+        B.kept_level.swap(grown[best_tree].level);
+        B.kept_dptr.swap(grown[best_tree].dptr);
+        grown.clear();
         if (B.auto_depth && forced_len <= 0) {
             B.all_roots();
             for (int64_t split : split_choices) {
@@ -1184,7 +1219,9 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     if (tree && exact_tree) {
         // keep the arborescence as found
     } else if (tree) {
-        B.prim(best_seeds);
+        h->parent.swap(B.kept_parent);
+        h->level.swap(B.kept_level);
+        h->dptr.swap(B.kept_dptr);
         B.tree_index();
         while (B.auto_depth && B.prune_last_round(best_len)) {  // part of the automatic policy only
         }
