@@ -259,6 +259,29 @@ def test_transposed_handle_is_the_adjoint(env):
     assert np.array_equal(got, orc.dense_from_csr(m2, n2, rowptr, colidx).T @ G2.astype(np.float64))
 
 
+def test_launches_of_many_waves_use_the_small_batch_build(env):
+    """A launch of 65,536 waves or more runs the build of the kernels with batches of 4 rows; the graphs of the other
+    tests in this file stay below that.  R-MAT at scale 18 with k = 128 (two work items per wave, 262,144 rows) is
+    above it for the row launch, and is still small enough to check every row against the oracle."""
+    torch, cbm = env
+    g = wl.make_graph("rmat", scale=18, edge_factor=16)
+    k = 128
+    for opts in (dict(), dict(max_depth=16, alpha=0)):
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, **opts)
+        s = cbm.cbm_stats(h)
+        assert s["num_tasks"] // 2 >= 65536
+        Xi = wl.integer_features(g.n, k, 9, lo=-2, hi=2)
+        ref = orc.spmm_csr(g.rowptr, g.colidx, Xi)
+        assert np.abs(ref).max() < 2 ** 24
+        assert np.array_equal(_run(env, "cbm_spmm", h, Xi, g.n).astype(np.float64), ref)
+        cbm.cbm_free(h)
+    hn = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=2)
+    Xg = wl.gaussian_features(g.n, k, 9)
+    assert row_scaled_error(_run(env, "cbm_spmm_normalized", hn, Xg, g.n), orc.spmm_csr_normalized(g.rowptr, g.colidx, Xg)) <= TOL
+    assert row_scaled_error(_run(env, "cbm_spmm_mean", hn, Xg, g.n),
+                            orc.spmm_csr_mean(*_csr(orc.adjacency_lists(g.n, g.rowptr, g.colidx, add_self_loops=True)[1:]), Xg)) <= TOL
+
+
 def test_degenerate_shapes(env):
     torch, cbm = env
     # empty matrix
