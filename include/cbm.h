@@ -251,13 +251,15 @@ cbm_status cbm_decompress(const cbm_handle* h, int64_t* rowptr, int32_t* colidx)
  */
 typedef struct {
     int32_t kind;           /* 0 = gather/update round, 1 = segments of split rows,
-                               2 = split-row combine, 3 = row-scale fix-up             */
+                               2 = split-row combine, 3 = deferred finish of rows that
+                               other work items read (row weight, self term, ReLU)       */
     int32_t level;          /* round for kinds 0 and 2, else 0                         */
     int64_t tasks;          /* work items in the launch                               */
     int64_t deltas;         /* delta entries gathered by the launch                   */
     int64_t algorithmic_bytes; /* bytes the method itself must move in this launch    */
     float milliseconds;
-    float reserved;
+    int32_t per_xcd;        /* 1 = the launch hands every XCD a work list of its own (segments
+                               by column range; a round in graph-locality order), else 0     */
 } cbm_launch_record;
 cbm_status cbm_profile_enable(cbm_handle* h, int32_t on);
 cbm_status cbm_profile_read(cbm_handle* h, cbm_launch_record* records, int32_t cap, int32_t* count);

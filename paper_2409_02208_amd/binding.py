@@ -53,7 +53,7 @@ class cbm_stats_t(C.Structure):
 
 class cbm_launch_record(C.Structure):
     _fields_ = [("kind", C.c_int32), ("level", C.c_int32), ("tasks", C.c_int64), ("deltas", C.c_int64),
-                ("algorithmic_bytes", C.c_int64), ("milliseconds", C.c_float), ("reserved", C.c_float)]
+                ("algorithmic_bytes", C.c_int64), ("milliseconds", C.c_float), ("per_xcd", C.c_int32)]
 
 
 _LIB = None
@@ -244,7 +244,7 @@ def cbm_profile_read(h: Handle) -> list:
     cnt = C.c_int32()
     _check(_lib().cbm_profile_read(h.ptr, recs, cap, C.byref(cnt)), "cbm_profile_read")
     return [dict(kind=r.kind, level=r.level, tasks=r.tasks, deltas=r.deltas,
-                 algorithmic_bytes=r.algorithmic_bytes, milliseconds=r.milliseconds)
+                 algorithmic_bytes=r.algorithmic_bytes, milliseconds=r.milliseconds, per_xcd=r.per_xcd)
             for r in recs[:min(cap, cnt.value)]]
 
 

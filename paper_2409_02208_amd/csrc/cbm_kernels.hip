@@ -572,6 +572,7 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
     if (h->num_slots > 0) {
         cbm_launch_record rec{};
         rec.kind = 1;
+        rec.per_xcd = 1;
         rec.tasks = h->num_slots;
         rec.deltas = h->seg_deltas;
         // the method's bytes only: the partial sums of split rows are this implementation's overhead
@@ -584,6 +585,7 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
         if (L.task_count > 0) {
             cbm_launch_record rec{};
             rec.kind = 0;
+            rec.per_xcd = L.by_xcd ? 1 : 0;
             rec.level = (int32_t)l + 1;
             rec.tasks = L.task_count;
             rec.deltas = L.deltas;

@@ -282,6 +282,26 @@ def test_launches_of_many_waves_use_the_small_batch_build(env):
                             orc.spmm_csr_mean(*_csr(orc.adjacency_lists(g.n, g.rowptr, g.colidx, add_self_loops=True)[1:]), Xg)) <= TOL
 
 
+def test_rounds_scheduled_by_graph_locality(env):
+    """Rounds of long work items on a square matrix are handed out per XCD in breadth-first order of the graph; a
+    nearest-neighbour graph with 100 neighbours has such rounds.  Every row against the oracle, and the launch records
+    must show that the per-XCD path was taken (and is not taken when switched off by a rectangular matrix)."""
+    torch, cbm = env
+    g = wl.make_graph("protein", n=20000, knn=100)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=2, max_depth=16)  # a tree, whatever it costs
+    cbm.cbm_profile_enable(h, True)
+    for k in (64, 256, 30):
+        Xg = wl.gaussian_features(g.n, k, 4)
+        got = _run(env, "cbm_spmm_normalized", h, Xg, g.n)
+        recs = cbm.cbm_profile_read(h)
+        assert any(r["kind"] == 0 and r["per_xcd"] == 1 for r in recs), recs
+        assert row_scaled_error(got, orc.spmm_csr_normalized(g.rowptr, g.colidx, Xg)) <= TOL
+    cbm.cbm_profile_enable(h, False)
+    Xi = wl.integer_features(g.n, 16, 4, lo=-2, hi=2)
+    hp = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=2, max_depth=16)
+    assert np.array_equal(_run(env, "cbm_spmm", hp, Xi, g.n).astype(np.float64), orc.spmm_csr(g.rowptr, g.colidx, Xi))
+
+
 def test_degenerate_shapes(env):
     torch, cbm = env
     # empty matrix
