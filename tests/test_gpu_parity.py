@@ -274,6 +274,8 @@ def test_launches_of_many_waves_use_the_small_batch_build(env):
         ref = orc.spmm_csr(g.rowptr, g.colidx, Xi)
         assert np.abs(ref).max() < 2 ** 24
         assert np.array_equal(_run(env, "cbm_spmm", h, Xi, g.n).astype(np.float64), ref)
+        Xr = np.ascontiguousarray(Xi[:, :126])        # not a multiple of four columns: the ragged variant of the same build
+        assert np.array_equal(_run(env, "cbm_spmm", h, Xr, g.n).astype(np.float64), ref[:, :126])
         cbm.cbm_free(h)
     hn = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=2)
     Xg = wl.gaussian_features(g.n, k, 9)
