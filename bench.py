@@ -297,10 +297,11 @@ def report(args, torch, cbm, wl, orc, csr_ref):
         log(f"graph {name}: n={g.n} nnz={g.nnz} ({time.perf_counter() - t0:.1f} s)")
         t0 = time.perf_counter()
         h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=d["alpha"], max_depth=args.max_depth,
-                          device_build=not args.host_build)
+                          host_search=args.host_build)
         tb = time.perf_counter() - t0
         t0 = time.perf_counter()   # the same build with the candidate search on the host threads, for the table only
-        cbm.cbm_free(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=d["alpha"], max_depth=args.max_depth))
+        cbm.cbm_free(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=d["alpha"], max_depth=args.max_depth,
+                                   host_search=True))
         tb_host = time.perf_counter() - t0
         hc = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=1)
         for k in ks:
@@ -342,7 +343,7 @@ def report(args, torch, cbm, wl, orc, csr_ref):
             results.append(dict(workload=name, gcn=gc))
         if name == "collaboration":  # the iterated product X_{t+1} = A X_t of the collaboration config
             hp = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=d["alpha"], max_depth=args.max_depth,
-                               device_build=not args.host_build)
+                               host_search=args.host_build)
             a = torch.from_numpy(wl.gaussian_features(g.n, 128, 5)).cuda()
             b = torch.empty_like(a)
 
@@ -389,7 +390,7 @@ def alpha_sweep(args, torch, cbm, wl):
         cbm.cbm_free(hc)
         for alpha in (0, 1, 2, 4, 8, 16, 32, 64):
             h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha, max_depth=16,
-                              device_build=not args.host_build)
+                              host_search=args.host_build)
             st = cbm.cbm_stats(h)
             ms = time_steps(torch, lambda: cbm.cbm_spmm_normalized(h, X, Y), args.steps, args.warmup)
             nd = st["num_delta_plus"] + st["num_delta_minus"]
@@ -470,7 +471,7 @@ def main():
     Xh = wl.gaussian_features(g.n, k, g.meta["seed"])
     t0 = time.perf_counter()
     h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha, max_depth=args.max_depth,
-                      device_build=not args.host_build)
+                      host_search=args.host_build)
     st = cbm.cbm_stats(h)
     log(f"cbm_build: {time.perf_counter() - t0:.1f} s, deltas={st['num_delta_plus'] + st['num_delta_minus']} "
         f"of nnz={st['nnz']}, roots={st['num_roots']}, depth={st['depth']}, rounds={st['rounds']}")
@@ -492,7 +493,7 @@ def main():
             gc = wl.make_graph("citation")
             dc = DEFAULTS["citation"]
             h2 = cbm.cbm_build(gc.n, gc.n, gc.rowptr, gc.colidx, add_self_loops=True, alpha=dc["alpha"],
-                               device_build=not args.host_build)
+                               host_search=args.host_build)
             h2c = cbm.cbm_build(gc.n, gc.n, gc.rowptr, gc.colidx, add_self_loops=True, max_depth=1)
             gcn = bench_gcn(torch, cbm, wl, orc, gc, h2, h2c, dc["gcn"], args.steps, args.warmup)
         log(f"GCN ({gcn['workload']}): {gcn['ms']:.4f} ms (CSR handle {gcn['ms_with_csr_handle']} ms)")

@@ -50,7 +50,12 @@ typedef enum {
                                     with which, the pattern of A A^T) on the GPU instead of the
                                     host threads; the chain of compression is the same.  Needs
                                     1 <= max_candidates <= 16 (the default qualifies); not with
-                                    CBM_FLAG_HOST_ONLY.                                         */
+                                    CBM_FLAG_HOST_ONLY or CBM_FLAG_HOST_SEARCH.  Without this
+                                    flag a matrix of 65536 rows or more is searched on the GPU
+                                    too when those conditions hold, and on the host threads if
+                                    the GPU cannot take it (the search needs up to 24 GB of
+                                    device memory while it runs); with it, that is an error.   */
+#define CBM_FLAG_HOST_SEARCH 16u /* keep the candidate search on the host threads              */
 
 #define CBM_FLAG_TRANSPOSE 8u /* compress the transpose: the handle holds A^T (n x m; (A v I)^T with
                                  add_self_loops) and every product and query works on that matrix.

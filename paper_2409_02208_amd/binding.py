@@ -16,6 +16,7 @@ CBM_FLAG_HOST_ONLY = 1
 CBM_FLAG_EXACT_TREE = 2
 CBM_FLAG_DEVICE_BUILD = 4
 CBM_FLAG_TRANSPOSE = 8
+CBM_FLAG_HOST_SEARCH = 16
 
 EXPORTS = [
     "cbm_build", "cbm_spmm", "cbm_spmm_normalized", "cbm_spmm_normalized_relu", "cbm_spmm_mean", "cbm_spmm_gin",
@@ -134,7 +135,7 @@ class Handle:
 def cbm_build(m: int, n: int, rowptr: np.ndarray, colidx: np.ndarray, *, alpha: int = 0,
               add_self_loops: bool = False, max_depth: int = 0, hub_cap: int = 0, max_candidates: int = 0,
               seed_roots: int = 0, num_threads: int = 0, device: int = -1, host_only: bool = False, exact_tree: bool = False,
-              device_build: bool = False, transpose: bool = False) -> Handle:
+              device_build: bool = False, transpose: bool = False, host_search: bool = False) -> Handle:
     rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
     colidx = np.ascontiguousarray(colidx, dtype=np.int32)
     if rowptr.shape != (m + 1,):
@@ -143,7 +144,8 @@ def cbm_build(m: int, n: int, rowptr: np.ndarray, colidx: np.ndarray, *, alpha: 
         raise ValueError("colidx shorter than rowptr[m]")
     opts = cbm_build_opts(alpha, int(add_self_loops), max_depth, hub_cap, max_candidates, seed_roots, num_threads, device,
                           (CBM_FLAG_HOST_ONLY if host_only else 0) | (CBM_FLAG_EXACT_TREE if exact_tree else 0) |
-                          (CBM_FLAG_DEVICE_BUILD if device_build else 0) | (CBM_FLAG_TRANSPOSE if transpose else 0))
+                          (CBM_FLAG_DEVICE_BUILD if device_build else 0) | (CBM_FLAG_TRANSPOSE if transpose else 0) |
+                          (CBM_FLAG_HOST_SEARCH if host_search else 0))
     out = C.c_void_p()
     _check(_lib().cbm_build(m, n, rowptr.ctypes.data, colidx.ctypes.data, C.byref(opts), C.byref(out)), "cbm_build")
     return Handle(out.value)

@@ -29,6 +29,7 @@ constexpr int32_t kDefaultHubCap = 512;
 constexpr int32_t kDefaultMaxCand = 8;
 constexpr int64_t kLocalityMinEntries = 32;  // mean entries per work item from which a round is scheduled by locality
 constexpr double kLocalityEntries = 230.0;   // such a round's bandwidth grows by 1/230 of the base per entry in a work item
+constexpr int64_t kDeviceSearchMinRows = 65536;  // from here on a handle bound for a GPU searches its candidates there
 constexpr int64_t kSampleMinRows = 65536;  // automatic mode samples the compressibility of matrices this large first
 constexpr int32_t kSplitLenDefault = 512;  // most delta entries in one segment of a split row
 constexpr int32_t kSplitMinDefault = 128;  // rows with more delta entries than this are split
@@ -187,6 +188,7 @@ struct Builder {
     std::vector<int64_t> optr;  // candidate edges bucketed by parent
     std::vector<int32_t> ochild, ow;
     bool device_candidates = false;  // run the candidate search on the GPU
+    bool device_optional = false;    // ... and fall back to the host threads if that fails
     bool locality = false;           // rounds of long work items will be scheduled by graph locality
     bool sample_first = false;       // estimate what a tree could save from a sample of rows before the full search
     bool skip_tree = false;          // the sample said: nothing to gain, store every row in full
@@ -406,11 +408,17 @@ cbm_status Builder::find_candidates() {
         std::vector<int32_t> cn, cy, cw;
         const cbm_status st = cbm_device_candidates(h->opts.device, m, n, rowptr, colidx, tptr.data(), trow.data(), hub_cap,
                                                     min_saving, max_cand, &cn, &cy, &cw);
-        if (st != CBM_OK) return st;
-        auto& out = cand_per_thread[0];
-        for (int64_t x = 0; x < m; ++x)
-            for (int32_t i = 0; i < cn[x]; ++i) out.push_back({(int32_t)x, cy[x * max_cand + i], cw[x * max_cand + i]});
-    } else {
+        if (st != CBM_OK && !device_optional) return st;
+        if (st != CBM_OK) {
+            if (verbose) std::fprintf(stderr, "[cbm_build] candidate search on the GPU failed (%d): host threads instead\n", (int)st);
+            device_candidates = false;
+        } else {
+            auto& out = cand_per_thread[0];
+            for (int64_t x = 0; x < m; ++x)
+                for (int32_t i = 0; i < cn[x]; ++i) out.push_back({(int32_t)x, cy[x * max_cand + i], cw[x * max_cand + i]});
+        }
+    }
+    if (!device_candidates) {
         parallel_chunks(nthreads, m, 64, [&](int64_t b, int64_t e, int tid) {
             auto& cnt = counters[tid];
             auto& out = cand_per_thread[tid];
@@ -1106,9 +1114,15 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     bool tree = B.max_depth != 1 && m > 1;
     B.locality = m == n && !std::getenv("CBM_NO_LOCALITY");
     const bool exact_tree = (o.flags & CBM_FLAG_EXACT_TREE) != 0;
-    if (o.flags & CBM_FLAG_DEVICE_BUILD) {
-        if ((o.flags & CBM_FLAG_HOST_ONLY) || B.max_cand < 1 || B.max_cand > 16) return CBM_ERR_INVALID_ARG;
+    if (o.flags & CBM_FLAG_DEVICE_BUILD) {  // asked for: an error if it cannot be had
+        if ((o.flags & (CBM_FLAG_HOST_ONLY | CBM_FLAG_HOST_SEARCH)) || B.max_cand < 1 || B.max_cand > 16) return CBM_ERR_INVALID_ARG;
         B.device_candidates = true;
+    } else if (!(o.flags & (CBM_FLAG_HOST_ONLY | CBM_FLAG_HOST_SEARCH)) && m >= kDeviceSearchMinRows && B.max_cand >= 1 &&
+               B.max_cand <= 16) {
+        // not asked for: a handle that is going to a GPU anyway searches there too when the matrix is large, and
+        // falls back to the host threads if the GPU cannot take it (memory); both give the same candidates
+        B.device_candidates = true;
+        B.device_optional = true;
     }
     if (tree && exact_tree) {
         if ((st = B.find_candidates()) != CBM_OK) return st;

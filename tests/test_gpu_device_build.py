@@ -36,7 +36,7 @@ def _csr(rows):
 
 
 def _same_tree(cbm, m, n, rowptr, colidx, **opts):
-    hh = cbm.cbm_build(m, n, rowptr, colidx, **opts)
+    hh = cbm.cbm_build(m, n, rowptr, colidx, host_search=True, **opts)
     hd = cbm.cbm_build(m, n, rowptr, colidx, device_build=True, **opts)
     th, td = cbm.cbm_get_tree(hh), cbm.cbm_get_tree(hd)
     for key in ("parent", "nplus", "nminus", "level"):
@@ -100,4 +100,7 @@ def test_device_build_argument_errors(env):
     assert e.value.status == 1
     with pytest.raises(cbm.CbmError) as e:
         cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, device_build=True, host_only=True, max_depth=16)
+    assert e.value.status == 1
+    with pytest.raises(cbm.CbmError) as e:
+        cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, device_build=True, host_search=True, max_depth=16)
     assert e.value.status == 1

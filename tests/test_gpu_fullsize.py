@@ -45,11 +45,14 @@ def test_full_size_products(env, name):
     hn = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha)
     s = cbm.cbm_stats(hn)
     assert s["num_delta_plus"] + s["num_delta_minus"] <= s["nnz"] and s["scalar_ops"] <= s["nnz"]
-    # the builder's candidate search on the GPU picks the same tree as the host search, at full size too
+    # the builder's candidate search on the GPU (the default from 65,536 rows on, forced here for the small graphs) picks
+    # the same tree as the search on the host threads, at full size too
     hd = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha, device_build=True)
-    th, td = cbm.cbm_get_tree(hn), cbm.cbm_get_tree(hd)
-    assert all(np.array_equal(th[key], td[key]) for key in th)
+    hh = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha, host_search=True)
+    tn, td, th = cbm.cbm_get_tree(hn), cbm.cbm_get_tree(hd), cbm.cbm_get_tree(hh)
+    assert all(np.array_equal(th[key], td[key]) and np.array_equal(th[key], tn[key]) for key in th)
     cbm.cbm_free(hd)
+    cbm.cbm_free(hh)
     for k in ks:
         X = wl.gaussian_features(g.n, k, g.meta["seed"])
         Xd = torch.from_numpy(X).cuda()
