@@ -44,7 +44,7 @@ constexpr double kLaunchUs = 7.0;
 constexpr double kEntryUs = 0.2;
 constexpr double kBytesPerUs = 6.0e6;
 constexpr double kRefRowBytes = 512.0;
-constexpr int64_t kPathChoices[] = {16, 32, 64, 128, 256, 512};
+constexpr int64_t kPathChoices[] = {16, 32, 64, 128, 256};
 
 long env_or(const char* name, long dflt) {
     const char* v = std::getenv(name);
