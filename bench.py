@@ -485,18 +485,26 @@ def main():
         cpu_csr = cpu_csr_omp_baseline(csr_ref, g, Xh, k)
         log(f"CPU OpenMP CSR: {cpu_csr['ms']:.1f} ms on {cpu_csr['threads']} threads")
 
-    gcn = None
+    gcn, gcn_more = None, []
     if not args.no_gcn:
         if d["gcn"] is not None:
             gcn = bench_gcn(torch, cbm, wl, orc, g, h, hc, d["gcn"], args.steps, args.warmup)
-        else:  # the timed graph has no GCN in its configuration: use the citation-like one (PubMed's shape)
-            gc = wl.make_graph("citation")
-            dc = DEFAULTS["citation"]
-            h2 = cbm.cbm_build(gc.n, gc.n, gc.rowptr, gc.colidx, add_self_loops=True, alpha=dc["alpha"],
-                               host_search=args.host_build)
-            h2c = cbm.cbm_build(gc.n, gc.n, gc.rowptr, gc.colidx, add_self_loops=True, max_depth=1)
-            gcn = bench_gcn(torch, cbm, wl, orc, gc, h2, h2c, dc["gcn"], args.steps, args.warmup)
-        log(f"GCN ({gcn['workload']}): {gcn['ms']:.4f} ms (CSR handle {gcn['ms_with_csr_handle']} ms)")
+        else:  # the timed graph has no GCN in its configuration: the two configurations that have one
+            for gname in ("citation", "protein"):   # PubMed's shape; the dense-neighbourhood graph
+                gc = wl.make_graph(gname)
+                dc = DEFAULTS[gname]
+                h2 = cbm.cbm_build(gc.n, gc.n, gc.rowptr, gc.colidx, add_self_loops=True, alpha=dc["alpha"],
+                                   host_search=args.host_build)
+                h2c = cbm.cbm_build(gc.n, gc.n, gc.rowptr, gc.colidx, add_self_loops=True, max_depth=1)
+                res = bench_gcn(torch, cbm, wl, orc, gc, h2, h2c, dc["gcn"], args.steps, args.warmup)
+                log(f"GCN ({res['workload']}): {res['ms']:.4f} ms (CSR handle {res['ms_with_csr_handle']:.4f} ms)")
+                cbm.cbm_free(h2)
+                cbm.cbm_free(h2c)
+                del gc
+                if gcn is None:
+                    gcn = res
+                else:
+                    gcn_more.append(res)
 
     out = {
         "metric": "CBM normalised product A_hat.X: achieved algorithmic HBM GB/s (with edges*k/s, GPU CSR SpMM and "
@@ -525,6 +533,7 @@ def main():
         "cbm_over_csr_speedup": r["speedup"],
         "cpu_csr_spmm_omp": cpu_csr,
         "gcn2": gcn,
+        "gcn2_more": gcn_more,
         "parity": {"max_row_scaled_error": r["parity_err"], "rows_checked": int(r["rows_checked"]), "tolerance": 1e-5},
         "cbm_stats": st,
         "paper_context": "paper: ~5x SpMM and up to 3x GCN inference over MKL CSR on a 16-core Xeon Gold 6130 "
