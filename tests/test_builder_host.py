@@ -303,3 +303,26 @@ def test_invariants_random_options(seed):
     if opts["max_depth"] > 0 and not opts["exact_tree"]:
         assert s["depth"] <= opts["max_depth"]
     cbm.cbm_free(h)
+
+
+def test_build_is_independent_of_the_thread_count():
+    """The candidate search, the transpose, the seeded tree growths and the entry stream run on several host threads;
+    the result must not depend on how many (same tree, same statistics, same decompressed matrix)."""
+    import workloads as wl
+
+    g = wl.make_graph("collaboration", n=30000)
+    ref = None
+    for nt in (1, 2, 5, 0):
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=2, add_self_loops=True, host_only=True, max_depth=16,
+                          num_threads=nt)
+        t = cbm.cbm_get_tree(h)
+        s = cbm.cbm_stats(h)
+        s.pop("build_seconds")
+        cur = (t, s, cbm.cbm_decompress(h))
+        if ref is None:
+            ref = cur
+        else:
+            assert all(np.array_equal(ref[0][k], cur[0][k]) for k in ref[0])
+            assert ref[1] == cur[1]
+            assert np.array_equal(ref[2][0], cur[2][0]) and np.array_equal(ref[2][1], cur[2][1])
+        cbm.cbm_free(h)

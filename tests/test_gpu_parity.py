@@ -304,6 +304,23 @@ def test_rounds_scheduled_by_graph_locality(env):
     assert np.array_equal(_run(env, "cbm_spmm", hp, Xi, g.n).astype(np.float64), orc.spmm_csr(g.rowptr, g.colidx, Xi))
 
 
+def test_product_is_independent_of_the_builder_thread_count(env, graphs):
+    """Same work lists whatever the number of host threads that built them: same rounding, bit for bit."""
+    torch, cbm = env
+    for name in ("collaboration", "rmat"):
+        g = graphs[name]
+        X = torch.from_numpy(wl.gaussian_features(g.n, 48, 6)).cuda()
+        ys = []
+        for nt in (1, 3, 0):
+            h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=1, max_depth=16, num_threads=nt)
+            Y = torch.empty_like(X)
+            cbm.cbm_spmm_normalized(h, X, Y)
+            torch.cuda.synchronize()
+            ys.append(Y)
+            cbm.cbm_free(h)
+        assert torch.equal(ys[0], ys[1]) and torch.equal(ys[0], ys[2])
+
+
 def test_degenerate_shapes(env):
     torch, cbm = env
     # empty matrix
