@@ -321,6 +321,19 @@ def test_product_is_independent_of_the_builder_thread_count(env, graphs):
         assert torch.equal(ys[0], ys[1]) and torch.equal(ys[0], ys[2])
 
 
+@pytest.mark.parametrize("k", [1000, 4096, 4099])
+def test_very_wide_features(env, k):
+    """Many column chunks per work item, aligned and ragged."""
+    torch, cbm = env
+    g = wl.tiny_graph()
+    X = wl.gaussian_features(g.n, k, 1)
+    ref = orc.spmm_csr_normalized(g.rowptr, g.colidx, X)
+    for opts in (dict(max_depth=16), dict()):
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, **opts)
+        assert row_scaled_error(_run(env, "cbm_spmm_normalized", h, X, g.n), ref) <= TOL
+        cbm.cbm_free(h)
+
+
 def test_degenerate_shapes(env):
     torch, cbm = env
     # empty matrix
