@@ -117,7 +117,7 @@ __device__ __forceinline__ void store_row(float* row, int c0, int k, Vec4 acc, b
 // flight while batch b is accumulated: a long path is a chain of dependent adds, but never a chain
 // of dependent loads.  Two builds of every variant: batches of 8 rows at 4 waves per SIMD for
 // launches with few, long work items (the loads in flight come from inside each item), batches
-// of 4 at 6 or more waves per SIMD for launches with many work items (they come from occupancy).
+// of 2 at 8 waves per SIMD for launches with many work items (they come from occupancy).
 // Some launches map workgroups to work items per XCD: workgroup b runs on XCD b mod 8 and takes its
 // items from that XCD's block of the task list -- the segments of one column range of X, or one share
 // of a round whose work items were put in graph-locality order.
@@ -127,12 +127,12 @@ struct CbmSegMap {
     int use;
 };
 
-// Waves per SIMD the register allocation is held to: 4 with batches of 8 rows, 6 with batches of 4 --
+// Waves per SIMD the register allocation is held to: 4 with batches of 8 rows, 8 with batches of 2 --
 // one less for the few variants that would otherwise spill registers.
 constexpr int level_min_waves(bool ragged, int lanes, int mode, int umax) {
     const bool weighted = mode >= 1 && mode <= 3;
     if (umax >= 8) return ((lanes == 16 || (ragged && lanes == 8)) && weighted) ? 3 : 4;
-    return (lanes == 8 && weighted) ? 5 : 6;
+    return 8;
 }
 
 template <bool RAGGED, int LANES, int MODE, int UMAX>
@@ -401,14 +401,14 @@ void launch_combine(const LaunchCtx& c, const CbmLevel& L) {
 using LevelFn = void (*)(const LaunchCtx&, const CbmLevel&);
 struct Variant {
     LevelFn level, combine, segments;  // batches of 8 rows
-    LevelFn level_many, segments_many;  // batches of 4 rows, higher occupancy: for launches of many work items
+    LevelFn level_many, segments_many;  // batches of 2 rows, full occupancy: for launches of many work items
     int group;                          // work items per wave
 };
 
 template <bool RAGGED, int LANES, int MODE>
 Variant variant() {
     return {launch_level<RAGGED, LANES, MODE, 8>, launch_combine<RAGGED, LANES, MODE>, launch_segments<RAGGED, LANES, MODE, 8>,
-            launch_level<RAGGED, LANES, MODE, 4>, launch_segments<RAGGED, LANES, MODE, 4>, 64 / LANES};
+            launch_level<RAGGED, LANES, MODE, 2>, launch_segments<RAGGED, LANES, MODE, 2>, 64 / LANES};
 }
 template <bool RAGGED, int LANES>
 Variant pick_mode(int mode) {
