@@ -92,3 +92,33 @@ def test_full_size_products(env, name):
     want = (np.diff(g.rowptr).astype(np.float64)[:, None] * X.astype(np.float64)).sum(axis=0)
     assert np.array_equal(colsum, want)
     cbm.cbm_free(h)
+
+
+def test_full_size_gcn_on_sampled_rows(env):
+    """The two-layer GCN of the protein configuration (256-256-112) at full size: the output rows of a sample of
+    nodes against the oracle, which needs the hidden layer only on those nodes' neighbourhoods."""
+    torch, cbm = env
+    g = wl.make_graph("protein")
+    f_in, hidden, f_out = 256, 256, 112
+    seed = g.meta["seed"]
+    X = wl.gaussian_features(g.n, f_in, seed)
+    W0, W1 = wl.glorot_uniform(f_in, hidden, seed), wl.glorot_uniform(hidden, f_out, seed)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=2)
+    out = torch.full((g.n, f_out), float("nan"), device="cuda")
+    ws = torch.empty(cbm.cbm_gcn2_workspace_bytes(h, f_in, hidden, f_out), dtype=torch.uint8, device="cuda")
+    cbm.cbm_gcn2_forward(h, *(torch.from_numpy(a).cuda() for a in (X, W0, W1)), out, ws)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(out).any())
+
+    rows = np.sort(np.random.default_rng(3).choice(g.n, size=16, replace=False))
+    d = np.diff(g.rowptr) + 1
+    # hidden layer on the closed neighbourhoods of the sampled rows
+    need = np.unique(np.concatenate([g.colidx[g.rowptr[i]:g.rowptr[i + 1]] for i in rows] + [rows]))
+    Z0 = X.astype(np.float64) @ W0.astype(np.float64)
+    H_need = np.maximum(orc.spmm_csr_normalized(g.rowptr, g.colidx, Z0, rows=need, d=d), 0.0)
+    Z1 = np.zeros((g.n, f_out))
+    Z1[need] = H_need @ W1.astype(np.float64)
+    ref = orc.spmm_csr_normalized(g.rowptr, g.colidx, Z1, rows=rows, d=d)      # reads Z1 only on `need`
+    got = out[torch.as_tensor(rows, device="cuda")].cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)
+    assert err.max() <= 1e-5, float(err.max())
