@@ -168,15 +168,25 @@ cbm_status cbm_build(int64_t m, int64_t n, const int64_t* rowptr, const int32_t*
  * and access instead of 128, not an error; it takes about 1.7x the time per
  * byte on a large graph, so pad the feature dimension to a multiple of 4 where
  * speed matters.
- * Not thread-safe per handle (rows with very long delta lists use scratch owned
- * by the handle, sized on first use for a given k).  That first use allocates:
- * call the product once with the widest k before capturing it in a HIP graph;
- * later calls with the same or a smaller k only launch kernels and can be
- * captured.  Per-launch profiling (cbm_profile_enable) records events and must
- * be off during capture.
+ * Rows with very long delta lists are summed in pieces through a scratch array owned
+ * by the handle (cbm_stats.num_split_rows > 0 says the handle has such rows).  Hence:
+ *  - one product at a time per handle: two products of one handle that run at the same
+ *    time (two host threads, or two streams) would share that scratch and race;
+ *  - the scratch is sized for the widest k seen so far.  A product with a wider k than
+ *    any before it frees and reallocates it (the free waits for the device), which is
+ *    not allowed under HIP-graph capture: call cbm_reserve(h, widest k) once beforehand;
+ *    after that, products with k <= that width only launch kernels and can be captured.
+ * Per-launch profiling (cbm_profile_enable) records events and must be off during capture.
  */
 cbm_status cbm_spmm(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
                     void* hip_stream);
+
+/*
+ * cbm_reserve -- size the handle's split-row scratch for products of up to max_k columns now, so
+ * that no later product with k <= max_k allocates (see cbm_spmm).  The handle's device must be
+ * current.  A handle without split rows needs no scratch: the call then does nothing.
+ */
+cbm_status cbm_reserve(cbm_handle* h, int32_t max_k);
 
 /*
  * cbm_spmm_normalized -- Y = D^-1/2 (A + I) D^-1/2 . X  (Eq. (1); Section 2.2,
@@ -223,6 +233,9 @@ cbm_status cbm_dense_matmul(int64_t M, int32_t N, int32_t K, const float* A, int
  *   row-major, densely packed (leading dimension = number of columns).
  *   workspace  device scratch of at least cbm_gcn2_workspace_bytes() bytes,
  *              caller-owned, 16-byte aligned.
+ * X, W0, W1, the workspace and out must not overlap one another where one is written
+ * (CBM_ERR_INVALID_ARG).  The handle's split-row scratch is sized for max(hidden, f_out)
+ * before the first kernel is enqueued (as cbm_reserve does).
  */
 cbm_status cbm_gcn2_forward(const cbm_handle* h, const float* X, int32_t f_in, const float* W0, int32_t hidden,
                             const float* W1, int32_t f_out, float* out, void* workspace, size_t workspace_bytes,

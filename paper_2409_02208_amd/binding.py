@@ -20,7 +20,7 @@ CBM_FLAG_HOST_SEARCH = 16
 
 EXPORTS = [
     "cbm_build", "cbm_spmm", "cbm_spmm_normalized", "cbm_spmm_normalized_relu", "cbm_spmm_mean", "cbm_spmm_gin",
-    "cbm_dense_matmul",
+    "cbm_dense_matmul", "cbm_reserve",
     "cbm_gcn2_forward", "cbm_gcn2_workspace_bytes", "cbm_stats", "cbm_get_tree", "cbm_decompress",
     "cbm_profile_enable", "cbm_profile_read", "cbm_free", "cbm_status_string", "cbm_last_error_detail",
 ]
@@ -75,6 +75,7 @@ def _lib():
         for name in ("cbm_spmm", "cbm_spmm_normalized", "cbm_spmm_normalized_relu", "cbm_spmm_mean"):
             getattr(lib, name).argtypes = [vp, f32p, i64, i32, f32p, i64, vp]
         lib.cbm_spmm_gin.argtypes = [vp, C.c_float, f32p, i64, i32, f32p, i64, vp]
+        lib.cbm_reserve.argtypes = [vp, i32]
         lib.cbm_dense_matmul.argtypes = [i64, i32, i32, f32p, i64, f32p, i64, f32p, i64, vp]
         lib.cbm_gcn2_forward.argtypes = [vp, f32p, i32, f32p, i32, f32p, i32, f32p, vp, C.c_size_t, vp]
         lib.cbm_gcn2_workspace_bytes.argtypes = [vp, i32, i32, i32]
@@ -183,6 +184,10 @@ def cbm_spmm_gin(h: Handle, eps: float, X, Y, stream=None):
         raise ValueError("X and Y must have the same number of columns")
     _check(_lib().cbm_spmm_gin(h.ptr, float(eps), xp, ldx, X.shape[1], yp, ldy, _stream_ptr(stream)), "cbm_spmm_gin")
     return Y
+
+
+def cbm_reserve(h: Handle, max_k: int):
+    _check(_lib().cbm_reserve(h.ptr, int(max_k)), "cbm_reserve")
 
 
 def cbm_dense_matmul(A, B, Cout, stream=None):

@@ -96,6 +96,15 @@ cbm_status cbm_spmm_gin(const cbm_handle* h, float eps, const float* X, int64_t 
     return cbm_launch_product(h, X, ldx, k, Y, ldy, CBM_EPI_SELF, 1.0f + eps, hip_stream);
 }
 
+cbm_status cbm_reserve(cbm_handle* h, int32_t max_k) {
+    if (!h || max_k <= 0) return CBM_ERR_INVALID_ARG;
+    if (!h->on_device) return CBM_ERR_STATE;
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess) return CBM_ERR_HIP;
+    if (cur != h->device) return CBM_ERR_STATE;
+    return cbm_reserve_scratch(h, max_k);
+}
+
 cbm_status cbm_dense_matmul(int64_t M, int32_t N, int32_t K, const float* A, int64_t lda, const float* B, int64_t ldb,
                             float* C, int64_t ldc, void* hip_stream) {
     if (M < 0 || N < 0 || K < 0 || lda < K || ldb < N || ldc < N) return CBM_ERR_INVALID_ARG;
@@ -121,11 +130,25 @@ cbm_status cbm_gcn2_forward(const cbm_handle* h, const float* X, int32_t f_in, c
         return CBM_ERR_INVALID_ARG;
     auto r = [](size_t b) { return (b + 255) & ~(size_t)255; };
     const int64_t n = h->n;
+    {   // out is written while the workspace is read, the workspace while X and the weights are read: none may overlap
+        struct Span {
+            uintptr_t b, e;
+        };
+        auto span = [](const void* p, size_t bytes) { return Span{(uintptr_t)p, (uintptr_t)p + bytes}; };
+        const Span wsp = span(workspace, workspace_bytes), outp = span(out, (size_t)n * f_out * 4);
+        const Span in[3] = {span(X, (size_t)n * f_in * 4), span(W0, (size_t)f_in * hidden * 4), span(W1, (size_t)hidden * f_out * 4)};
+        auto overlap = [](Span a, Span b) { return a.b < b.e && b.b < a.e; };
+        if (overlap(wsp, outp)) return CBM_ERR_INVALID_ARG;
+        for (const Span& s : in)
+            if (overlap(s, wsp) || overlap(s, outp)) return CBM_ERR_INVALID_ARG;
+    }
+    cbm_status st;
+    // both products share the handle's split-row scratch: size it once for the wider of the two, before anything is enqueued
+    if ((st = cbm_reserve_scratch(h, hidden > f_out ? hidden : f_out)) != CBM_OK) return st;
     char* ws = (char*)workspace;
     float* Z0 = (float*)ws;
     float* H = (float*)(ws + r((size_t)n * hidden * 4));
     float* Z1 = (float*)(ws + 2 * r((size_t)n * hidden * 4));
-    cbm_status st;
     if ((st = cbm_launch_gemm(n, hidden, f_in, X, f_in, W0, hidden, Z0, hidden, hip_stream)) != CBM_OK) return st;
     if ((st = cbm_launch_product(h, Z0, hidden, hidden, H, hidden, CBM_EPI_ROWSCALE_RELU, 0.0f, hip_stream)) != CBM_OK)
         return st;

@@ -50,6 +50,8 @@ long env_or(const char* name, long dflt) {
     const char* v = std::getenv(name);
     return v ? std::atol(v) : dflt;
 }
+// a tuning knob from the environment, held to the range the work lists can encode
+long env_clamped(const char* name, long dflt, long lo, long hi) { return std::min(hi, std::max(lo, env_or(name, dflt))); }
 
 template <class F>
 void parallel_chunks(int nthreads, int64_t total, int64_t chunk, F&& fn) {
@@ -884,8 +886,8 @@ double Builder::csr_cost() const {
 
 // Write the entry stream and the work-item lists for the paths chosen by plan().
 cbm_status Builder::emit(int32_t nrounds) {
-    const int phases = (int)env_or("CBM_PHASES", kPhasesDefault);
-    const int64_t fine_min = env_or("CBM_FINE_MIN", kFineMinDefault);
+    const int phases = (int)env_clamped("CBM_PHASES", kPhasesDefault, 1, 64);
+    const int64_t fine_min = env_clamped("CBM_FINE_MIN", kFineMinDefault, 1, (long)CBM_TASK_LEN_MASK);
     // rows that a row of ANOTHER work item is compressed against keep their unscaled sum in Y
     std::vector<uint8_t> internal(m, 0);
     h->internal_rows.clear();
@@ -926,6 +928,8 @@ cbm_status Builder::emit(int32_t nrounds) {
             R.deltas += dlen(v);
             ++R.rows_written;
         }
+        // the entry count shares a word with the work item's flags
+        if (at - start > (int64_t)CBM_TASK_LEN_MASK) return CBM_ERR_UNSUPPORTED;
         paths.push_back({x, start});
         rtasks[round[x]].push_back({x, y, (uint32_t)start, (uint32_t)(at - start)});
         R.parent_reads += y >= 0;
@@ -1061,8 +1065,9 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     B.max_cand = o.max_candidates == 0 ? kDefaultMaxCand : o.max_candidates;
     B.verbose = std::getenv("CBM_VERBOSE") != nullptr;
     B.last = t0;
-    B.split_len = env_or("CBM_SPLIT_LEN", kSplitLenDefault);
-    B.split_min = env_or("CBM_SPLIT_MIN", kSplitMinDefault);
+    // segments and unsplit rows both have to fit the 24-bit entry count of a work item
+    B.split_len = env_clamped("CBM_SPLIT_LEN", kSplitLenDefault, 1, 1 << 20);
+    B.split_min = env_clamped("CBM_SPLIT_MIN", kSplitMinDefault, 1, 1 << 20);
     h->m = m;
     h->n = n;
     h->eff_alpha = B.alpha;
@@ -1144,7 +1149,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     }
     if (tree && !exact_tree && B.skip_tree) tree = false;
     if (tree && !exact_tree) {
-        const int64_t forced_len = env_or("CBM_PATH_MAX", 0);
+        const int64_t forced_len = env_clamped("CBM_PATH_MAX", 0, 0, 1 << 20);
         const int64_t forced_seeds = o.seed_roots > 0 ? o.seed_roots : o.seed_roots < 0 ? 0 : env_or("CBM_SEED_ROOTS", -1);
         double best_us = 1e300;
         // the trees grown from 0, m/128, m/32, m/8 seeded roots, side by side (or the one the caller asked for)

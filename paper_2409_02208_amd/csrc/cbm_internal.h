@@ -106,6 +106,8 @@ cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t
                                  const int64_t* tptr, const int32_t* trow, int64_t hub_cap, int64_t min_saving,
                                  int32_t keep, std::vector<int32_t>* out_n, std::vector<int32_t>* out_y,
                                  std::vector<int32_t>* out_w);
+// grow the handle's split-row scratch to k columns (no-op when it is wide enough or no row is split)
+cbm_status cbm_reserve_scratch(const cbm_handle* h, int32_t k);
 cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
                               CbmEpilogue epi, float self_weight, void* stream);
 // dense fp32 MFMA matmul (cbm_gemm.hip)

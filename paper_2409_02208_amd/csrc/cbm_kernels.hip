@@ -338,6 +338,7 @@ struct LaunchCtx {
     int k;
     float* Y;
     int64_t ldy;
+    float* scratch;  // partial sums of split rows: the handle's own array, or the library's static one
     int64_t ld_scratch;
     hipStream_t stream;
     const float* ws;  // per-entry weights of the stream (MODE 1/2)
@@ -361,14 +362,14 @@ void launch_level(const LaunchCtx& c, const CbmLevel& L) {
         map.use = 1;
         dim3 grid((unsigned)(CBM_XCD * ((most + 4 * G - 1) / (4 * G))), (unsigned)ychunks);
         hipLaunchKernelGGL((cbm_level_kernel<RAGGED, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream, c.h->d_tasks,
-                           (int64_t)c.h->tasks.size(), map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.h->d_scratch,
+                           (int64_t)c.h->tasks.size(), map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.scratch,
                            c.ld_scratch, c.ws, c.rw, c.self_w, c.k);
         return;
     }
     dim3 grid((unsigned)((L.task_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
     hipLaunchKernelGGL((cbm_level_kernel<RAGGED, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream,
                        c.h->d_tasks + L.task_begin, L.task_count, map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy,
-                       c.h->d_scratch, c.ld_scratch, c.ws, c.rw, c.self_w, c.k);
+                       c.scratch, c.ld_scratch, c.ws, c.rw, c.self_w, c.k);
 }
 // all segments of all split rows, one block of work items per XCD
 template <bool RAGGED, int LANES, int MODE, int UMAX>
@@ -385,7 +386,7 @@ void launch_segments(const LaunchCtx& c, const CbmLevel&) {
     map.use = 1;
     dim3 grid((unsigned)(CBM_XCD * ((most + 4 * G - 1) / (4 * G))), (unsigned)ychunks);
     hipLaunchKernelGGL((cbm_level_kernel<RAGGED, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream, c.h->d_tasks,
-                       (int64_t)c.h->tasks.size(), map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.h->d_scratch,
+                       (int64_t)c.h->tasks.size(), map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.scratch,
                        c.ld_scratch, c.ws, c.rw, c.self_w, c.k);
 }
 template <bool RAGGED, int LANES, int MODE>
@@ -394,7 +395,7 @@ void launch_combine(const LaunchCtx& c, const CbmLevel& L) {
     const int ychunks = (c.k + LANES * 4 - 1) / (LANES * 4);
     dim3 grid((unsigned)((L.comb_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
     hipLaunchKernelGGL((cbm_combine_kernel<RAGGED, LANES, MODE>), grid, dim3(256), 0, c.stream,
-                       c.h->d_comb + L.comb_begin, L.comb_count, c.X, c.ldx, c.Y, c.ldy, c.h->d_scratch,
+                       c.h->d_comb + L.comb_begin, L.comb_count, c.X, c.ldx, c.Y, c.ldy, c.scratch,
                        c.ld_scratch, c.rw, c.self_w, c.k);
 }
 
@@ -522,6 +523,19 @@ void cbm_release_device(cbm_handle* h) {
     h->on_device = false;
 }
 
+// Make the handle's split-row scratch at least num_slots x k floats (rounded up to four columns).
+cbm_status cbm_reserve_scratch(const cbm_handle* h, int32_t k) {
+    const int64_t ld_scratch = ((int64_t)k + 3) & ~(int64_t)3;
+    if (h->num_slots <= 0 || h->scratch_k >= ld_scratch) return CBM_OK;
+    // hipFree waits for the device: no product enqueued earlier is still reading the old array when it goes
+    if (h->d_scratch) hipFree(h->d_scratch);
+    h->d_scratch = nullptr;
+    h->scratch_k = 0;
+    HIP_TRY(hipMalloc((void**)&h->d_scratch, (size_t)h->num_slots * ld_scratch * sizeof(float)), CBM_ERR_ALLOC);
+    h->scratch_k = ld_scratch;
+    return CBM_OK;
+}
+
 cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
                               CbmEpilogue epi, float self_weight, void* stream_) {
     hipStream_t stream = (hipStream_t)stream_;
@@ -529,15 +543,10 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
     HIP_TRY(hipGetDevice(&cur), CBM_ERR_HIP);
     if (cur != h->device) return CBM_ERR_STATE;  // the caller's current device must be the handle's
 
-    // scratch rows for split rows, sized for this k on first use
+    // scratch rows for split rows: sized by cbm_reserve, else for this k on first use
     const int64_t ld_scratch = ((int64_t)k + 3) & ~(int64_t)3;
-    if (h->num_slots > 0 && h->scratch_k < ld_scratch) {
-        if (h->d_scratch) hipFree(h->d_scratch);
-        h->d_scratch = nullptr;
-        h->scratch_k = 0;
-        HIP_TRY(hipMalloc((void**)&h->d_scratch, (size_t)h->num_slots * ld_scratch * sizeof(float)), CBM_ERR_ALLOC);
-        h->scratch_k = ld_scratch;
-    }
+    if (const cbm_status st = cbm_reserve_scratch(h, k); st != CBM_OK) return st;
+    float* const scratch = h->d_scratch;
 
     // every lane holds four columns; rows that all start on 16-byte boundaries and hold a multiple of four columns
     // take the aligned variant (128-bit accesses), anything else the ragged one (32-bit accesses, strided columns)
@@ -565,7 +574,7 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
     const int64_t ychunks = ((int64_t)k + lanes * 4 - 1) / (lanes * 4);
     auto many = [&](int64_t items) { return items / var.group * ychunks >= many_waves; };
     const bool wcol = mode == 1 || mode == 2, wrow = wcol || mode == 3;
-    const LaunchCtx ctx{h, X, ldx, k, Y, ldy, ld_scratch, stream, h->d_wstream, mode == 3 ? h->d_rinv : h->d_dinv, self_weight};
+    const LaunchCtx ctx{h, X, ldx, k, Y, ldy, scratch, ld_scratch, stream, h->d_wstream, mode == 3 ? h->d_rinv : h->d_dinv, self_weight};
     const int64_t rowb = 4 * (int64_t)k;
     const int64_t per_delta = rowb + 4 + (wcol ? 4 : 0);
     const int64_t per_row = rowb + 4 + (wrow ? 4 : 0) + (mode == 4 ? rowb : 0);  // Y write, marker, weight, own X row

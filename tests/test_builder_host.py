@@ -227,6 +227,30 @@ def test_error_paths_return_status_codes():
     assert lib.cbm_spmm(h.ptr, 16, 2, 4, 32, 4, None) == 1
 
 
+def test_tuning_knobs_from_the_environment_are_held_in_range(monkeypatch):
+    """Out-of-range values of the builder's environment knobs must not reach the work lists: zero sub-ranges
+    would divide by zero, and an entry count of 2^24 or more would spill into a work item's flag bits."""
+    rng = np.random.default_rng(3)
+    n = 5000
+    rows = [sorted(rng.choice(n, size=2000, replace=False).tolist()), [1, 2, 3], []]
+    rowptr, colidx = _csr(rows)
+    monkeypatch.setenv("CBM_PHASES", "0")
+    h = cbm.cbm_build(3, n, rowptr, colidx, host_only=True, max_depth=16)
+    s = _check_invariants(3, n, rowptr, colidx, h, 0, False)
+    assert s["num_split_rows"] == 1
+    monkeypatch.delenv("CBM_PHASES")
+    for name in ("CBM_SPLIT_MIN", "CBM_SPLIT_LEN", "CBM_PATH_MAX", "CBM_FINE_MIN"):
+        monkeypatch.setenv(name, str(1 << 26))
+        h = cbm.cbm_build(3, n, rowptr, colidx, host_only=True, max_depth=16)
+        _check_invariants(3, n, rowptr, colidx, h, 0, False)
+        monkeypatch.delenv(name)
+    for name in ("CBM_SPLIT_MIN", "CBM_SPLIT_LEN"):
+        monkeypatch.setenv(name, "-5")
+        h = cbm.cbm_build(3, n, rowptr, colidx, host_only=True, max_depth=16)
+        _check_invariants(3, n, rowptr, colidx, h, 0, False)
+        monkeypatch.delenv(name)
+
+
 @pytest.mark.parametrize("name,kw", [("citation", dict(n=3000, p_in=3e-3, p_out=2e-4)), ("collaboration", dict(n=3000)),
                                      ("protein", dict(n=1200, knn=20)), ("rmat", dict(scale=10, edge_factor=8))])
 def test_invariants_on_reduced_workloads(name, kw):

@@ -406,6 +406,51 @@ def test_argument_errors_on_device_handle(env, graphs):
     assert e.value.status == 1
 
 
+def test_reserve_sizes_the_split_row_scratch_before_capture(env):
+    # cbm_reserve instead of a first eager product: a handle WITH split rows is captured at once, and the replay is exact
+    torch, cbm = env
+    rng = np.random.default_rng(5)
+    n = 3000
+    rows = [sorted(rng.choice(n, size=int(s), replace=False).tolist()) for s in rng.integers(0, 700, size=400)]
+    rowptr, colidx = _csr(rows)
+    h = cbm.cbm_build(len(rows), n, rowptr, colidx, max_depth=16)
+    assert cbm.cbm_stats(h)["num_split_rows"] > 0
+    X = wl.integer_features(n, 48, 3)
+    Xd = torch.from_numpy(X).cuda()
+    Y = torch.full((len(rows), 48), float("nan"), device="cuda")
+    cbm.cbm_reserve(h, 48)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cbm.cbm_spmm(h, Xd, Y)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert np.array_equal(Y.cpu().numpy().astype(np.float64), orc.spmm_csr(rowptr, colidx, X))
+    with pytest.raises(cbm.CbmError) as e:
+        cbm.cbm_reserve(h, 0)
+    assert e.value.status == 1
+
+
+def test_gcn2_rejects_overlapping_buffers(env, graphs):
+    torch, cbm = env
+    g = graphs["tiny"]
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=16)
+    f_in, hidden, f_out = 8, 8, 8
+    nb = cbm.cbm_gcn2_workspace_bytes(h, f_in, hidden, f_out)
+    ws = torch.zeros(nb + g.n * f_out * 4, dtype=torch.uint8, device="cuda")
+    X = torch.zeros((g.n, f_in), device="cuda")
+    W0 = torch.zeros((f_in, hidden), device="cuda")
+    W1 = torch.zeros((hidden, f_out), device="cuda")
+    out = torch.zeros((g.n, f_out), device="cuda")
+    inside = ws[:g.n * f_out * 4].view(torch.float32).view(g.n, f_out)   # lies inside the workspace
+    for args in ((X, W0, W1, inside, ws), (inside, W0, W1, out, ws), (X, W0, W1, X, ws[:nb])):
+        with pytest.raises(cbm.CbmError) as e:
+            cbm.cbm_gcn2_forward(h, *args)
+        assert e.value.status == 1
+    cbm.cbm_gcn2_forward(h, X, W0, W1, out, ws[:nb])
+    torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("M,N,K", [(1000, 64, 500), (777, 3, 64), (513, 112, 256), (256, 256, 256), (130, 33, 7),
                                    (1, 1, 1), (300, 200, 37)])
 def test_dense_matmul(env, M, N, K):
