@@ -182,6 +182,25 @@ cbm_status cbm_spmm(const cbm_handle* h, const float* X, int64_t ldx, int32_t k,
                     void* hip_stream);
 
 /*
+ * cbm_spmm_noalloc -- cbm_spmm for callers that cannot allocate device memory: code under HIP-graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the
+ * same result as cbm_spmm, but the partial sums of split rows go to a 64 MiB array that is part of the
+ * library's device code instead of a scratch the handle allocates; the call makes no hipMalloc / hipFree
+ * and no other allocating call.
+ *   Limit: (segments the handle's split rows are cut into -- one scratch row each, at most
+ *   cbm_stats.num_tasks) x (k rounded up to a multiple of 4) floats must fit 64 MiB = 16,777,216 floats,
+ *   else CBM_ERR_UNSUPPORTED (cbm_last_error_detail gives the numbers); a handle without split rows
+ *   (cbm_stats.num_split_rows == 0) always fits.
+ *   CBM_ERR_STATE while per-launch profiling is on (it creates events).
+ * Every GPU the library runs on holds one such array until the process ends, and every call on that GPU
+ * shares it, whatever the handle: calls that overlap in time on one GPU (two streams, two host threads)
+ * race on it -- run them one after the other.  Nothing in it has to be cleared between calls: a product
+ * writes every scratch row it later reads.
+ */
+cbm_status cbm_spmm_noalloc(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
+                            void* hip_stream);
+
+/*
  * cbm_reserve -- size the handle's split-row scratch for products of up to max_k columns now, so
  * that no later product with k <= max_k allocates (see cbm_spmm).  The handle's device must be
  * current.  A handle without split rows needs no scratch: the call then does nothing.

@@ -19,7 +19,7 @@ CBM_FLAG_TRANSPOSE = 8
 CBM_FLAG_HOST_SEARCH = 16
 
 EXPORTS = [
-    "cbm_build", "cbm_spmm", "cbm_spmm_normalized", "cbm_spmm_normalized_relu", "cbm_spmm_mean", "cbm_spmm_gin",
+    "cbm_build", "cbm_spmm", "cbm_spmm_noalloc", "cbm_spmm_normalized", "cbm_spmm_normalized_relu", "cbm_spmm_mean", "cbm_spmm_gin",
     "cbm_dense_matmul", "cbm_reserve",
     "cbm_gcn2_forward", "cbm_gcn2_workspace_bytes", "cbm_stats", "cbm_get_tree", "cbm_decompress",
     "cbm_profile_enable", "cbm_profile_read", "cbm_free", "cbm_status_string", "cbm_last_error_detail",
@@ -72,7 +72,7 @@ def _lib():
         lib = C.CDLL(LIB_PATH)
         vp, i64, i32, f32p = C.c_void_p, C.c_int64, C.c_int32, C.c_void_p
         lib.cbm_build.argtypes = [i64, i64, vp, vp, C.POINTER(cbm_build_opts), C.POINTER(vp)]
-        for name in ("cbm_spmm", "cbm_spmm_normalized", "cbm_spmm_normalized_relu", "cbm_spmm_mean"):
+        for name in ("cbm_spmm", "cbm_spmm_noalloc", "cbm_spmm_normalized", "cbm_spmm_normalized_relu", "cbm_spmm_mean"):
             getattr(lib, name).argtypes = [vp, f32p, i64, i32, f32p, i64, vp]
         lib.cbm_spmm_gin.argtypes = [vp, C.c_float, f32p, i64, i32, f32p, i64, vp]
         lib.cbm_reserve.argtypes = [vp, i32]
@@ -163,6 +163,10 @@ def _product(fn_name, h: Handle, X, Y, stream):
 
 def cbm_spmm(h: Handle, X, Y, stream=None):
     return _product("cbm_spmm", h, X, Y, stream)
+
+
+def cbm_spmm_noalloc(h: Handle, X, Y, stream=None):
+    return _product("cbm_spmm_noalloc", h, X, Y, stream)
 
 
 def cbm_spmm_normalized(h: Handle, X, Y, stream=None):

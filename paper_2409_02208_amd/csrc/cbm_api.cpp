@@ -65,6 +65,13 @@ cbm_status cbm_spmm(const cbm_handle* h, const float* X, int64_t ldx, int32_t k,
     return cbm_launch_product(h, X, ldx, k, Y, ldy, CBM_EPI_NONE, 0.0f, hip_stream);
 }
 
+cbm_status cbm_spmm_noalloc(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
+                            void* hip_stream) {
+    cbm_status st = check_product_args(h, X, ldx, k, Y, ldy);
+    if (st != CBM_OK) return st;
+    return cbm_launch_product(h, X, ldx, k, Y, ldy, CBM_EPI_NONE, 0.0f, hip_stream, /*static_scratch=*/true);
+}
+
 cbm_status cbm_spmm_normalized(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
                                void* hip_stream) {
     cbm_status st = check_product_args(h, X, ldx, k, Y, ldy);

@@ -109,7 +109,8 @@ cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t
 // grow the handle's split-row scratch to k columns (no-op when it is wide enough or no row is split)
 cbm_status cbm_reserve_scratch(const cbm_handle* h, int32_t k);
 cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
-                              CbmEpilogue epi, float self_weight, void* stream);
+                              CbmEpilogue epi, float self_weight, void* stream, bool static_scratch = false);
+size_t cbm_static_scratch_bytes();
 // dense fp32 MFMA matmul (cbm_gemm.hip)
 cbm_status cbm_launch_gemm(int64_t M, int32_t N, int32_t K, const float* A, int64_t lda, const float* B, int64_t ldb,
                            float* C, int64_t ldc, void* stream);

@@ -15,6 +15,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
+#include <mutex>
 
 #include "cbm_internal.h"
 
@@ -27,7 +28,35 @@
         }                                                         \
     } while (0)
 
+// Partial sums of split rows for cbm_spmm_noalloc: the callers of that entry point cannot allocate, so the
+// library brings this array along.  Every GPU the library runs on holds its own copy until the process ends.
+// In host code the name is only a handle for hipGetSymbolAddress -- never a device address.
+#define CBM_STATIC_SCRATCH_FLOATS (16 * 1024 * 1024)  // 64 MiB
+static __device__ __align__(256) float cbm_static_scratch[CBM_STATIC_SCRATCH_FLOATS];
+
 namespace {
+
+// device address of cbm_static_scratch on each GPU (each holds the array at an address of its own)
+constexpr int kMaxDevices = 64;
+float* g_static_scratch[kMaxDevices] = {};
+std::mutex g_static_scratch_mutex;
+
+// Address of the static scratch on `device`, which must be the current device; resolved once per device.
+cbm_status static_scratch_address(int device, float** out) {
+    if (device < 0 || device >= kMaxDevices) return CBM_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (!g_static_scratch[device]) {
+        float* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(cbm_static_scratch)), CBM_ERR_HIP);
+        if (!ptr) {
+            cbm_set_error_detail("hipGetSymbolAddress(cbm_static_scratch)", "null address");
+            return CBM_ERR_HIP;
+        }
+        g_static_scratch[device] = ptr;
+    }
+    *out = g_static_scratch[device];
+    return CBM_OK;
+}
 
 // Four columns of a row: what one lane holds.
 struct alignas(16) Vec4 {
@@ -496,6 +525,14 @@ cbm_status cbm_upload(cbm_handle* h) {
             return CBM_ERR_HIP;
         }
     }
+    {   // set-up is the place to look up the static scratch of this GPU, so that cbm_spmm_noalloc need not
+        float* unused = nullptr;
+        if (static_scratch_address(dev, &unused) != CBM_OK) {
+            cbm_release_device(h);
+            if (cur != dev) hipSetDevice(cur);
+            return CBM_ERR_HIP;
+        }
+    }
     h->on_device = true;
     if (cur != dev) hipSetDevice(cur);
     return CBM_OK;
@@ -536,17 +573,37 @@ cbm_status cbm_reserve_scratch(const cbm_handle* h, int32_t k) {
     return CBM_OK;
 }
 
+size_t cbm_static_scratch_bytes() { return (size_t)CBM_STATIC_SCRATCH_FLOATS * sizeof(float); }
+
 cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
-                              CbmEpilogue epi, float self_weight, void* stream_) {
+                              CbmEpilogue epi, float self_weight, void* stream_, bool static_scratch) {
     hipStream_t stream = (hipStream_t)stream_;
     int cur = -1;
     HIP_TRY(hipGetDevice(&cur), CBM_ERR_HIP);
     if (cur != h->device) return CBM_ERR_STATE;  // the caller's current device must be the handle's
 
-    // scratch rows for split rows: sized by cbm_reserve, else for this k on first use
     const int64_t ld_scratch = ((int64_t)k + 3) & ~(int64_t)3;
-    if (const cbm_status st = cbm_reserve_scratch(h, k); st != CBM_OK) return st;
-    float* const scratch = h->d_scratch;
+    float* scratch = nullptr;
+    if (static_scratch) {
+        // nothing on this path allocates: the partial sums go to the library's static array, which every call on
+        // this GPU shares.  Segments overwrite their scratch rows in full before the combine launches read them,
+        // so nothing has to be cleared between calls.
+        if (h->profiling) return CBM_ERR_STATE;  // per-launch events are created on the fly
+        if (h->num_slots > 0) {
+            if ((uint64_t)h->num_slots * (uint64_t)ld_scratch > (uint64_t)CBM_STATIC_SCRATCH_FLOATS) {
+                char msg[160];
+                std::snprintf(msg, sizeof(msg), "%lld scratch rows of %lld floats exceed the static scratch of %lld floats",
+                              (long long)h->num_slots, (long long)ld_scratch, (long long)CBM_STATIC_SCRATCH_FLOATS);
+                cbm_set_error_detail("cbm_spmm_noalloc", msg);
+                return CBM_ERR_UNSUPPORTED;
+            }
+            if (const cbm_status st = static_scratch_address(cur, &scratch); st != CBM_OK) return st;
+        }
+    } else {
+        // scratch rows for split rows: sized by cbm_reserve, else for this k on first use
+        if (const cbm_status st = cbm_reserve_scratch(h, k); st != CBM_OK) return st;
+        scratch = h->d_scratch;
+    }
 
     // every lane holds four columns; rows that all start on 16-byte boundaries and hold a multiple of four columns
     // take the aligned variant (128-bit accesses), anything else the ragged one (32-bit accesses, strided columns)
