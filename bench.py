@@ -198,7 +198,7 @@ def counter_child(args):
             if last is not None:
                 cbm.cbm_free(last[1])
             last = (name, cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=DEFAULTS[name]["alpha"],
-                                        max_depth=args.max_depth, host_search=args.host_build))
+                                        max_depth=args.max_depth, host_search=args.host_build, column_blocks=args.column_blocks))
         h = last[1]
         X = torch.randn((g.n, k), device="cuda")
         Y = torch.empty((g.n, k), device="cuda")
@@ -227,7 +227,7 @@ def run_counter_children(args, cache_dir):
         d = os.path.join(cache_dir, "pmc_" + tag)
         cmd = ["timeout", "-s", "KILL", "240", prof, "--pmc", *counters, "--output-format", "csv", "-d", d, "-o", "p", "--",
                sys.executable, os.path.abspath(__file__), "--counter-child", "--graph-cache", cache_dir,
-               "--rmat-scale", str(args.rmat_scale), "--max-depth", str(args.max_depth)] + (["--host-build"] if args.host_build else [])
+               "--rmat-scale", str(args.rmat_scale), "--max-depth", str(args.max_depth), "--column-blocks", str(args.column_blocks)] + (["--host-build"] if args.host_build else [])
         t0 = time.perf_counter()
         env = dict(os.environ, TMPDIR="/tmp")
         r = subprocess.run(cmd, cwd="/tmp", env=env, capture_output=True, text=True)
@@ -461,10 +461,10 @@ def bench_product(torch, cbm, orc, g, h, hc, Xh, k, steps, warmup, workload, cou
                 build_seconds=st["build_seconds"], stats=st)
 
 
-def bench_chain(torch, cbm, orc, g, alpha, max_depth, host_build, steps, iterations=10, k=128):
+def bench_chain(torch, cbm, orc, g, alpha, max_depth, host_build, steps, iterations=10, k=128, column_blocks=0):
     """X_{t+1} = A X_t, `iterations` products in a row (the collaboration configuration's second operation): the
     compression is paid once, every iterate reuses it."""
-    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=alpha, max_depth=max_depth, host_search=host_build)
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=alpha, max_depth=max_depth, host_search=host_build, column_blocks=column_blocks)
     hc = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, max_depth=1)
     X0 = np.random.default_rng(5).integers(-1, 2, size=(g.n, k)).astype(np.float32)  # small integers: ten iterates stay finite
     a = torch.from_numpy(X0).cuda()
@@ -584,7 +584,7 @@ def report(args, torch, cbm, wl, orc, csr_ref):
         log(f"graph {name}: n={g.n} nnz={g.nnz} ({time.perf_counter() - t0:.1f} s)")
         t0 = time.perf_counter()
         h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=d["alpha"], max_depth=args.max_depth,
-                          host_search=args.host_build)
+                          host_search=args.host_build, column_blocks=args.column_blocks)
         tb = time.perf_counter() - t0
         t0 = time.perf_counter()   # the same build with the candidate search on the host threads, for the table only
         cbm.cbm_free(cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=d["alpha"], max_depth=args.max_depth,
@@ -720,6 +720,7 @@ def main():
     ap.add_argument("--alpha", type=int, default=-1)
     ap.add_argument("--max-depth", type=int, default=0)
     ap.add_argument("--rmat-scale", type=int, default=21)
+    ap.add_argument("--column-blocks", type=int, default=0, help="build the CBM handles column-blocked with this many column ranges")
     ap.add_argument("--host-build", action="store_true", help="run the builder's candidate search on the host threads, not on the GPU")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baselines")
     ap.add_argument("--no-gcn", action="store_true", help="skip the GCN inference timing")
@@ -802,7 +803,7 @@ def run(args, wl, store, counters, counters_note):
     Xh = wl.gaussian_features(g.n, k, g.meta["seed"])
     t0 = time.perf_counter()
     h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha, max_depth=args.max_depth,
-                      host_search=args.host_build)
+                      host_search=args.host_build, column_blocks=args.column_blocks)
     st = cbm.cbm_stats(h)
     log(f"cbm_build: {time.perf_counter() - t0:.1f} s, deltas={st['num_delta_plus'] + st['num_delta_minus']} "
         f"of nnz={st['nnz']}, roots={st['num_roots']}, depth={st['depth']}, rounds={st['rounds']}")
@@ -833,13 +834,14 @@ def run(args, wl, store, counters, counters_note):
             g2 = store.get(name, keep=False)
             d2 = DEFAULTS[name]
             h2 = cbm.cbm_build(g2.n, g2.n, g2.rowptr, g2.colidx, add_self_loops=True, alpha=d2["alpha"], max_depth=args.max_depth,
-                               host_search=args.host_build)
+                               host_search=args.host_build, column_blocks=args.column_blocks)
             h2c = cbm.cbm_build(g2.n, g2.n, g2.rowptr, g2.colidx, add_self_loops=True, max_depth=1)
             X2 = wl.gaussian_features(g2.n, d2["k"], g2.meta["seed"])
             products_more.append(slim(bench_product(torch, cbm, orc, g2, h2, h2c, X2, d2["k"], args.steps, args.warmup, name,
                                                     counted(name, d2["k"]), ceiling)))
             if name == "collaboration":
-                products_more.append(bench_chain(torch, cbm, orc, g2, d2["alpha"], args.max_depth, args.host_build, args.steps))
+                products_more.append(bench_chain(torch, cbm, orc, g2, d2["alpha"], args.max_depth, args.host_build, args.steps,
+                                                 column_blocks=args.column_blocks))
                 log(f"collaboration A.X x10: {products_more[-1]['ms_total']:.4f} ms (GPU CSR {products_more[-1]['gpu_csr_ms_total']:.4f} ms)")
             if d2["gcn"] is not None and not args.no_gcn and name != "tiny":
                 res = bench_gcn(torch, cbm, wl, orc, g2, h2, h2c, d2["gcn"], args.steps, args.warmup)
@@ -852,7 +854,7 @@ def run(args, wl, store, counters, counters_note):
             cbm.cbm_free(h2c)
             del g2, X2
     elif not args.no_gcn and d["gcn"] is not None:
-        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha, max_depth=args.max_depth, host_search=args.host_build)
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=alpha, max_depth=args.max_depth, host_search=args.host_build, column_blocks=args.column_blocks)
         hc = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, max_depth=1)
         gcn = bench_gcn(torch, cbm, wl, orc, g, h, hc, d["gcn"], args.steps, args.warmup)
 
@@ -885,7 +887,7 @@ def run(args, wl, store, counters, counters_note):
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{g.name} ({g.meta['recipe']}), A_hat.X, k={k}", "n": g.n, "nnz": g.nnz, "k": k,
-                   "alpha": alpha, "max_depth_option": args.max_depth, "tree_depth": st["depth"], "rounds": st["rounds"],
+                   "alpha": alpha, "max_depth_option": args.max_depth, "column_blocks": max(1, args.column_blocks), "tree_depth": st["depth"], "rounds": st["rounds"],
                    "seed": g.meta["seed"]},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,

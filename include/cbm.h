@@ -105,6 +105,13 @@ typedef enum {
  *                picks among 0, m/128, m/32, m/8); -1 = none; > 0 = that many.
  * num_threads    Host threads for the build.  0 = all hardware threads.
  * device         HIP device that will own the arrays.  -1 = current device.
+ * flags          CBM_FLAG_* bits.
+ * column_blocks  0 or 1 = the format of the paper: one tree over whole rows.  B > 1 = column-blocked CBM (the
+ *                column-splitting idea that Section 1.1 credits to a related format): the columns are cut
+ *                into B equal ranges, the part of every row inside a range is a row of its own, and the
+ *                compression tree is grown over all B m part-rows, so two rows that are alike only inside one
+ *                range can still share; a product sums the B partial rows of each row in a last launch.  Costs B
+ *                partial rows (written, then read) per matrix row and product.  Not with CBM_FLAG_TRANSPOSE.
  */
 typedef struct {
     int32_t alpha;
@@ -116,6 +123,7 @@ typedef struct {
     int32_t num_threads;
     int32_t device;
     uint32_t flags;
+    int32_t column_blocks;
 } cbm_build_opts;
 
 typedef struct {
@@ -135,6 +143,11 @@ typedef struct {
     int32_t add_self_loops;
     int32_t rounds;          /* dependent kernel launches per product (<= depth)      */
     double build_seconds;
+    int32_t column_blocks;   /* 1, or B for a column-blocked handle: the tree then spans
+                                B m part-rows; num_roots, num_internal, depth and the
+                                delta counts are those of the part-rows, and scalar_ops
+                                includes the (B - 1) m additions of the block sum        */
+    int32_t reserved_;
 } cbm_stats_t;
 
 /*
@@ -268,7 +281,9 @@ cbm_status cbm_stats(const cbm_handle* h, cbm_stats_t* out);
  * cbm_get_tree -- the chain of compression, host arrays of m entries each (any
  * may be NULL): parent[x] = row that x is compressed against, -1 for the virtual
  * null row; nplus / nminus = |Delta+|, |Delta-| of the edge (parent[x], x);
- * level[x] = depth of x, 1 for rows stored in full.
+ * level[x] = depth of x, 1 for rows stored in full.  For a column-blocked handle (column_blocks = B > 1)
+ * every array has B m entries: entry b m + i is the part of row i inside column range b, and parents are
+ * part-row indices.
  */
 cbm_status cbm_get_tree(const cbm_handle* h, int32_t* parent, int32_t* nplus, int32_t* nminus, int32_t* level);
 
@@ -289,7 +304,8 @@ cbm_status cbm_decompress(const cbm_handle* h, int64_t* rowptr, int32_t* colidx)
 typedef struct {
     int32_t kind;           /* 0 = gather/update round, 1 = segments of split rows,
                                2 = split-row combine, 3 = deferred finish of rows that
-                               other work items read (row weight, self term, ReLU)       */
+                               other work items read (row weight, self term, ReLU),
+                               4 = sum of the partial rows of a column-blocked handle    */
     int32_t level;          /* round for kinds 0 and 2, else 0                         */
     int64_t tasks;          /* work items in the launch                               */
     int64_t deltas;         /* delta entries gathered by the launch                   */

@@ -38,7 +38,7 @@ class cbm_build_opts(C.Structure):
     _fields_ = [("alpha", C.c_int32), ("add_self_loops", C.c_int32), ("max_depth", C.c_int32),
                 ("hub_cap", C.c_int32), ("max_candidates", C.c_int32), ("seed_roots", C.c_int32),
                 ("num_threads", C.c_int32),
-                ("device", C.c_int32), ("flags", C.c_uint32)]
+                ("device", C.c_int32), ("flags", C.c_uint32), ("column_blocks", C.c_int32)]
 
 
 class cbm_stats_t(C.Structure):
@@ -46,7 +46,8 @@ class cbm_stats_t(C.Structure):
                 ("num_delta_minus", C.c_int64), ("num_roots", C.c_int64), ("num_internal", C.c_int64),
                 ("scalar_ops", C.c_int64), ("num_tasks", C.c_int64), ("num_split_rows", C.c_int64),
                 ("bytes_csr", C.c_int64), ("bytes_cbm", C.c_int64), ("depth", C.c_int32), ("alpha", C.c_int32),
-                ("add_self_loops", C.c_int32), ("rounds", C.c_int32), ("build_seconds", C.c_double)]
+                ("add_self_loops", C.c_int32), ("rounds", C.c_int32), ("build_seconds", C.c_double),
+                ("column_blocks", C.c_int32), ("reserved_", C.c_int32)]
 
     def as_dict(self) -> dict:
         return {f: getattr(self, f) for f, _ in self._fields_}
@@ -136,7 +137,8 @@ class Handle:
 def cbm_build(m: int, n: int, rowptr: np.ndarray, colidx: np.ndarray, *, alpha: int = 0,
               add_self_loops: bool = False, max_depth: int = 0, hub_cap: int = 0, max_candidates: int = 0,
               seed_roots: int = 0, num_threads: int = 0, device: int = -1, host_only: bool = False, exact_tree: bool = False,
-              device_build: bool = False, transpose: bool = False, host_search: bool = False) -> Handle:
+              device_build: bool = False, transpose: bool = False, host_search: bool = False,
+              column_blocks: int = 0) -> Handle:
     rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
     colidx = np.ascontiguousarray(colidx, dtype=np.int32)
     if rowptr.shape != (m + 1,):
@@ -146,7 +148,7 @@ def cbm_build(m: int, n: int, rowptr: np.ndarray, colidx: np.ndarray, *, alpha: 
     opts = cbm_build_opts(alpha, int(add_self_loops), max_depth, hub_cap, max_candidates, seed_roots, num_threads, device,
                           (CBM_FLAG_HOST_ONLY if host_only else 0) | (CBM_FLAG_EXACT_TREE if exact_tree else 0) |
                           (CBM_FLAG_DEVICE_BUILD if device_build else 0) | (CBM_FLAG_TRANSPOSE if transpose else 0) |
-                          (CBM_FLAG_HOST_SEARCH if host_search else 0))
+                          (CBM_FLAG_HOST_SEARCH if host_search else 0), column_blocks)
     out = C.c_void_p()
     _check(_lib().cbm_build(m, n, rowptr.ctypes.data, colidx.ctypes.data, C.byref(opts), C.byref(out)), "cbm_build")
     return Handle(out.value)
@@ -231,7 +233,8 @@ def cbm_stats(h: Handle) -> dict:
 
 
 def cbm_get_tree(h: Handle):
-    m = cbm_stats(h)["m"]
+    s = cbm_stats(h)
+    m = s["m"] * max(1, s["column_blocks"])
     arrs = [np.empty(m, dtype=np.int32) for _ in range(4)]
     _check(_lib().cbm_get_tree(h.ptr, *[a.ctypes.data for a in arrs]), "cbm_get_tree")
     return dict(zip(("parent", "nplus", "nminus", "level"), arrs))

@@ -109,7 +109,7 @@ cbm_status cbm_reserve(cbm_handle* h, int32_t max_k) {
     int cur = -1;
     if (hipGetDevice(&cur) != hipSuccess) return CBM_ERR_HIP;
     if (cur != h->device) return CBM_ERR_STATE;
-    return cbm_reserve_scratch(h, max_k);
+    return cbm_reserve_scratch(h, max_k);  // (a column-blocked handle: its partial rows and the inner scratch)
 }
 
 cbm_status cbm_dense_matmul(int64_t M, int32_t N, int32_t K, const float* A, int64_t lda, const float* B, int64_t ldb,
@@ -171,6 +171,7 @@ cbm_status cbm_stats(const cbm_handle* h, cbm_stats_t* out) {
 
 cbm_status cbm_get_tree(const cbm_handle* h, int32_t* parent, int32_t* nplus, int32_t* nminus, int32_t* level) {
     if (!h) return CBM_ERR_INVALID_ARG;
+    if (h->blocks > 1) h = h->inner;  // the tree over the B m part-rows
     const size_t bytes = (size_t)h->m * sizeof(int32_t);
     if (parent && bytes) std::memcpy(parent, h->parent.data(), bytes);
     if (nplus && bytes) std::memcpy(nplus, h->nplus.data(), bytes);
@@ -188,11 +189,13 @@ cbm_status cbm_profile_enable(cbm_handle* h, int32_t on) {
     if (!h) return CBM_ERR_INVALID_ARG;
     if (!h->on_device) return CBM_ERR_STATE;
     h->profiling = on != 0;
+    if (h->inner) h->inner->profiling = on != 0;
     return CBM_OK;
 }
 
 cbm_status cbm_profile_read(cbm_handle* h, cbm_launch_record* records, int32_t cap, int32_t* count) {
     if (!h || !count || cap < 0 || (cap > 0 && !records)) return CBM_ERR_INVALID_ARG;
+    if (h->inner) h = h->inner;  // a column-blocked handle's launches are recorded where they are made
     const size_t nrec = h->prof_records.size();
     if (h->prof_events.size() != 2 * nrec) return CBM_ERR_STATE;
     for (size_t i = 0; i < nrec; ++i) {
@@ -210,6 +213,10 @@ cbm_status cbm_profile_read(cbm_handle* h, cbm_launch_record* records, int32_t c
 void cbm_free(cbm_handle* h) {
     if (!h) return;
     cbm_release_device(h);
+    if (h->inner) {
+        cbm_release_device(h->inner);
+        delete h->inner;
+    }
     delete h;
 }
 

@@ -1,4 +1,4 @@
-// Candidate search of the builder on the GPU.
+// The builder's GPU side: the candidate search, and the delta lists of the chosen tree.
 //
 // The compression tree is chosen among "candidate" edges (y, x): rows y that share columns with
 // row x, ranked by the Hamming distance of Lemma 2.1, w(y,x) = nnz(a_x) + nnz(a_y) - 2 |a_x n a_y|.
@@ -312,6 +312,68 @@ __global__ __launch_bounds__(256) void cbm_candidates_kernel(const CandArgs a) {
     }
 }
 
+
+// ---- delta lists (Eq. (2)) on the GPU -----------------------------------------------------------------
+// One wave per row x with tree parent y: Delta+ = a_x \ a_y, Delta- = a_y \ a_x.  Both lists are sorted, so
+// membership is a binary search in the other list; a wave takes 64 elements at a time, and the elements that
+// are NOT found keep their order in the output (ballot + prefix count).  COUNT = true only counts.
+__device__ __forceinline__ bool sorted_contains(const int32_t* __restrict__ a, int64_t n, int32_t v) {
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (a[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    return lo < n && a[lo] == v;
+}
+
+template <bool COUNT>
+__global__ __launch_bounds__(256) void cbm_delta_kernel(int64_t m, const int64_t* __restrict__ rowptr,
+                                                        const int32_t* __restrict__ colidx,
+                                                        const int32_t* __restrict__ parent, int32_t* __restrict__ nplus,
+                                                        int32_t* __restrict__ nminus, const int64_t* __restrict__ dptr,
+                                                        uint32_t* __restrict__ dcol) {
+    const int64_t x = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (x >= m) return;
+    const int lane = threadIdx.x & 63;
+    const int32_t y = parent[x];
+    const int32_t* ax = colidx + rowptr[x];
+    const int64_t nx = rowptr[x + 1] - rowptr[x];
+    if (y < 0) {  // compressed against the virtual null row: the row itself
+        if (COUNT) {
+            if (lane == 0) {
+                nplus[x] = (int32_t)nx;
+                nminus[x] = 0;
+            }
+        } else {
+            for (int64_t i = lane; i < nx; i += 64) dcol[dptr[x] + i] = (uint32_t)ax[i];
+        }
+        return;
+    }
+    const int32_t* ay = colidx + rowptr[y];
+    const int64_t ny = rowptr[y + 1] - rowptr[y];
+    int64_t at = COUNT ? 0 : dptr[x];
+    int32_t count[2] = {0, 0};
+    for (int side = 0; side < 2; ++side) {  // 0: elements of a_x missing from a_y; 1: elements of a_y missing from a_x
+        const int32_t* a = side ? ay : ax;
+        const int32_t* b = side ? ax : ay;
+        const int64_t na = side ? ny : nx, nb = side ? nx : ny;
+        for (int64_t i0 = 0; i0 < na; i0 += 64) {
+            const int64_t i = i0 + lane;
+            const int32_t v = i < na ? a[i] : 0;
+            const bool out = i < na && !sorted_contains(b, nb, v);
+            const unsigned long long mask = __ballot(out);
+            if (!COUNT && out)
+                dcol[at + __popcll(mask & ((1ull << lane) - 1ull))] = (uint32_t)v | (side ? CBM_DELTA_MINUS : 0u);
+            at += __popcll(mask);
+            count[side] += __popcll(mask);
+        }
+    }
+    if (COUNT && lane == 0) {
+        nplus[x] = count[0];
+        nminus[x] = count[1];
+    }
+}
+
 struct DeviceBuffers {
     std::vector<void*> ptrs;
     ~DeviceBuffers() {
@@ -503,6 +565,60 @@ cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t
     CAND_TRY(hipMemcpy(out_y->data(), a.out_y, (size_t)m * keep * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
     CAND_TRY(hipMemcpy(out_w->data(), a.out_w, (size_t)m * keep * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
     lap("download");
+    if (cur != dev) hipSetDevice(cur);
+    return CBM_OK;
+}
+
+// Delta lists of every tree edge on the GPU: the same lists, in the same order, as the host merge.
+cbm_status cbm_device_deltas(int device, int64_t m, const int64_t* rowptr, const int32_t* colidx, const int32_t* parent,
+                             std::vector<int32_t>* nplus, std::vector<int32_t>* nminus, std::vector<int64_t>* dptr,
+                             std::vector<uint32_t>* dcol) {
+    nplus->assign(m, 0);
+    nminus->assign(m, 0);
+    dptr->assign(m + 1, 0);
+    dcol->clear();
+    if (m == 0) return CBM_OK;
+    int cur = -1, dev = device;
+    {
+        hipError_t e = hipGetDevice(&cur);
+        if (e != hipSuccess) {
+            cbm_set_error_detail("hipGetDevice", hipGetErrorString(e));
+            return CBM_ERR_HIP;
+        }
+    }
+    if (dev < 0) dev = cur;
+    if (cur != dev) CAND_TRY(hipSetDevice(dev), CBM_ERR_HIP);
+    const int64_t nnz = rowptr[m];
+    DeviceBuffers buf;
+    int64_t *d_rowptr = nullptr, *d_dptr = nullptr;
+    int32_t *d_colidx = nullptr, *d_parent = nullptr, *d_np = nullptr, *d_nm = nullptr;
+    uint32_t* d_dcol = nullptr;
+    CAND_TRY(buf.alloc(&d_rowptr, (size_t)m + 1), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&d_colidx, (size_t)nnz), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&d_parent, (size_t)m), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&d_np, (size_t)m), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&d_nm, (size_t)m), CBM_ERR_ALLOC);
+    CAND_TRY(buf.alloc(&d_dptr, (size_t)m + 1), CBM_ERR_ALLOC);
+    CAND_TRY(hipMemcpy(d_rowptr, rowptr, ((size_t)m + 1) * 8, hipMemcpyHostToDevice), CBM_ERR_HIP);
+    if (nnz > 0) CAND_TRY(hipMemcpy(d_colidx, colidx, (size_t)nnz * 4, hipMemcpyHostToDevice), CBM_ERR_HIP);
+    CAND_TRY(hipMemcpy(d_parent, parent, (size_t)m * 4, hipMemcpyHostToDevice), CBM_ERR_HIP);
+    const dim3 grid((unsigned)((m + 3) / 4));
+    hipLaunchKernelGGL(cbm_delta_kernel<true>, grid, dim3(256), 0, 0, m, d_rowptr, d_colidx, d_parent, d_np, d_nm,
+                       (const int64_t*)nullptr, (uint32_t*)nullptr);
+    CAND_TRY(hipGetLastError(), CBM_ERR_HIP);
+    CAND_TRY(hipMemcpy(nplus->data(), d_np, (size_t)m * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
+    CAND_TRY(hipMemcpy(nminus->data(), d_nm, (size_t)m * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
+    for (int64_t x = 0; x < m; ++x) (*dptr)[x + 1] = (*dptr)[x] + (*nplus)[x] + (*nminus)[x];
+    const int64_t nd = (*dptr)[m];
+    dcol->resize((size_t)nd);
+    if (nd > 0) {
+        CAND_TRY(buf.alloc(&d_dcol, (size_t)nd), CBM_ERR_ALLOC);
+        CAND_TRY(hipMemcpy(d_dptr, dptr->data(), ((size_t)m + 1) * 8, hipMemcpyHostToDevice), CBM_ERR_HIP);
+        hipLaunchKernelGGL(cbm_delta_kernel<false>, grid, dim3(256), 0, 0, m, d_rowptr, d_colidx, d_parent, d_np, d_nm,
+                           (const int64_t*)d_dptr, d_dcol);
+        CAND_TRY(hipGetLastError(), CBM_ERR_HIP);
+        CAND_TRY(hipMemcpy(dcol->data(), d_dcol, (size_t)nd * 4, hipMemcpyDeviceToHost), CBM_ERR_HIP);
+    }
     if (cur != dev) hipSetDevice(cur);
     return CBM_OK;
 }

@@ -668,8 +668,20 @@ void Builder::arborescence() {
     }
 }
 
-// Delta lists (Eq. (2)) of every tree edge by list merge.
+// Delta lists (Eq. (2)) of every tree edge by list merge -- or, for a handle that searched its candidates on the GPU,
+// by the GPU's kernel, which writes the same lists in the same order (the host merge is the fallback).
 void Builder::delta_lists() {
+    bool any_parent = false;  // with every row stored in full the lists are the rows themselves: nothing to send anywhere
+    for (int64_t x = 0; x < m && !any_parent; ++x) any_parent = h->parent[x] >= 0;
+    if (device_candidates && any_parent) {
+        const cbm_status st = cbm_device_deltas(h->opts.device, m, rowptr, colidx, h->parent.data(), &h->nplus, &h->nminus,
+                                                &h->dptr, &h->dcol);
+        if (st == CBM_OK) {
+            lap("delta lists (GPU)");
+            return;
+        }
+        if (verbose) std::fprintf(stderr, "[cbm_build] delta lists on the GPU failed (%d): host threads instead\n", (int)st);
+    }
     h->nplus.assign(m, 0);
     h->nminus.assign(m, 0);
     parallel_chunks(nthreads, m, 1024, [&](int64_t b, int64_t e, int) {
@@ -1044,12 +1056,106 @@ cbm_status Builder::emit(int32_t nrounds) {
 
 }  // namespace
 
+// Column-blocked CBM: the columns are cut into B equal ranges and the part of every row inside a range becomes a row
+// of its own; the B m part-rows, stacked block after block (part-row b m + i = row i inside range b), are compressed
+// as ONE matrix by the builder above -- its candidate search only ever pairs rows that share columns, so trees form
+// inside ranges -- and a product is the sum of the B partial rows of every row.  The format lives in h->inner.
+static cbm_status cbm_build_blocked(int64_t m, int64_t n, const int64_t* in_rowptr, const int32_t* in_colidx, cbm_handle* h) {
+    auto t0 = std::chrono::steady_clock::now();
+    const cbm_build_opts& o = h->opts;
+    const int64_t B = o.column_blocks;
+    if (o.flags & CBM_FLAG_TRANSPOSE) return CBM_ERR_INVALID_ARG;
+    if (o.add_self_loops && m != n) return CBM_ERR_INVALID_ARG;
+    if (B > 64 || B * m > (int64_t)CBM_ENTRY_INDEX_MASK || n > (int64_t)CBM_ENTRY_INDEX_MASK) return CBM_ERR_UNSUPPORTED;
+    Builder P;  // borrowed for its CSR checks and the A v I step
+    P.h = h;
+    P.m = m;
+    P.n = n;
+    P.nthreads = o.num_threads > 0 ? o.num_threads : (int)std::max(1u, std::thread::hardware_concurrency());
+    cbm_status st = P.validate(in_rowptr, in_colidx);
+    if (st != CBM_OK) return st;
+    P.rowptr = in_rowptr;
+    P.colidx = in_colidx;
+    if (o.add_self_loops) P.self_loops(in_rowptr, in_colidx);
+    const int64_t nnz = P.rowptr[m];
+    if (nnz >= (int64_t)UINT32_MAX) return CBM_ERR_UNSUPPORTED;
+    h->m = m;
+    h->n = n;
+    h->blocks = (int32_t)B;
+    h->square_self_loops = o.add_self_loops != 0;
+    // the part-rows, block after block
+    std::vector<int64_t> srp((size_t)(B * m) + 1, 0);
+    std::vector<int32_t> sci((size_t)nnz);
+    auto lo_of = [&](int64_t b) { return (int32_t)((b * n + B - 1) / B); };  // block b = columns [lo_of(b), lo_of(b + 1))
+    parallel_chunks(P.nthreads, m, 4096, [&](int64_t r0, int64_t r1, int) {
+        for (int64_t i = r0; i < r1; ++i) {
+            const int32_t* row = P.colidx + P.rowptr[i];
+            const int32_t* end = P.colidx + P.rowptr[i + 1];
+            for (int64_t b = 0; b < B; ++b) {
+                const int32_t* lo = std::lower_bound(row, end, lo_of(b));
+                const int32_t* hi = std::lower_bound(lo, end, lo_of(b + 1));
+                srp[(size_t)(b * m + i) + 1] = hi - lo;
+            }
+        }
+    });
+    for (int64_t v = 0; v < B * m; ++v) srp[v + 1] += srp[v];
+    parallel_chunks(P.nthreads, m, 4096, [&](int64_t r0, int64_t r1, int) {
+        for (int64_t i = r0; i < r1; ++i) {
+            const int32_t* row = P.colidx + P.rowptr[i];
+            const int32_t* end = P.colidx + P.rowptr[i + 1];
+            for (int64_t b = 0; b < B; ++b) {
+                const int32_t* lo = std::lower_bound(row, end, lo_of(b));
+                const int32_t* hi = std::lower_bound(lo, end, lo_of(b + 1));
+                std::copy(lo, hi, sci.begin() + srp[(size_t)(b * m + i)]);
+            }
+        }
+    });
+    cbm_handle* in = new cbm_handle();
+    h->inner = in;  // owned from here on: freed with the outer handle, also on failure
+    in->opts = o;
+    in->opts.column_blocks = 0;
+    in->opts.add_self_loops = 0;
+    st = cbm_build_host(B * m, n, srp.data(), sci.data(), in);
+    if (st != CBM_OK) return st;
+    // weights by index: an entry's index is a column (< n) or a part-row b m + i, whose weights are those of row i
+    std::vector<float> dinv, rinv(m);
+    for (int64_t i = 0; i < m; ++i) {
+        const int64_t len = P.rowptr[i + 1] - P.rowptr[i];
+        rinv[i] = len > 0 ? (float)(1.0 / (double)len) : 0.0f;
+    }
+    in->rinv.resize((size_t)(B * m));
+    for (int64_t v = 0; v < B * m; ++v) in->rinv[v] = rinv[v % m];
+    if (h->square_self_loops) {  // D = row sums of A v I
+        in->square_self_loops = true;
+        in->dinv.resize((size_t)(B * m));
+        for (int64_t v = 0; v < B * m; ++v) {
+            const int64_t i = v % m;
+            in->dinv[v] = (float)(1.0 / std::sqrt((double)(P.rowptr[i + 1] - P.rowptr[i])));
+        }
+        in->stats.bytes_cbm += 4 * (int64_t)in->dinv.size();
+    }
+    h->rownnz.resize(m);
+    for (int64_t i = 0; i < m; ++i) h->rownnz[i] = (int32_t)(P.rowptr[i + 1] - P.rowptr[i]);
+    cbm_stats_t& s = h->stats;
+    s = in->stats;
+    s.m = m;
+    s.n = n;
+    s.nnz = nnz;
+    s.scalar_ops += (B - 1) * m;  // the additions of the block sum
+    s.bytes_csr = 8 * (m + 1) + 4 * in_rowptr[m];
+    s.add_self_loops = o.add_self_loops != 0;
+    s.column_blocks = (int32_t)B;
+    s.build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    return CBM_OK;
+}
+
 cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const int32_t* in_colidx, cbm_handle* h) {
     auto t0 = std::chrono::steady_clock::now();
     const cbm_build_opts& o = h->opts;
     if (o.alpha < 0 || o.max_depth < -1 || o.hub_cap < -1 || o.max_candidates < -1 || o.seed_roots < -1 ||
-        o.num_threads < 0)
+        o.num_threads < 0 || o.column_blocks < 0)
         return CBM_ERR_INVALID_ARG;
+    if (o.column_blocks > 1) return cbm_build_blocked(m, n, in_rowptr, in_colidx, h);
     if (m > (int64_t)CBM_ENTRY_INDEX_MASK || n > (int64_t)CBM_ENTRY_INDEX_MASK) return CBM_ERR_UNSUPPORTED;
     if (o.add_self_loops && m != n) return CBM_ERR_INVALID_ARG;
     Builder B;
@@ -1285,11 +1391,28 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     s.rounds = nrounds;
     s.alpha = B.alpha;
     s.add_self_loops = o.add_self_loops != 0;
+    s.column_blocks = 1;
     s.build_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     return CBM_OK;
 }
 
 cbm_status cbm_decompress_host(const cbm_handle* h, int64_t* rowptr, int32_t* colidx) {
+    if (h->blocks > 1) {  // rebuild the part-rows from the inner format, then put every row's parts back together
+        const cbm_handle* in = h->inner;
+        const int64_t m = h->m, B = h->blocks;
+        std::vector<int64_t> srp((size_t)(B * m) + 1);
+        std::vector<int32_t> sci((size_t)std::max<int64_t>(1, in->stats.nnz));
+        const cbm_status st = cbm_decompress_host(in, srp.data(), sci.data());
+        if (st != CBM_OK) return st;
+        rowptr[0] = 0;
+        for (int64_t i = 0; i < m; ++i) {
+            int32_t* out = colidx + rowptr[i];
+            for (int64_t b = 0; b < B; ++b)  // ranges ascend, so the parts in block order are the sorted row
+                out = std::copy(sci.begin() + srp[(size_t)(b * m + i)], sci.begin() + srp[(size_t)(b * m + i) + 1], out);
+            rowptr[i + 1] = out - colidx;
+        }
+        return CBM_OK;
+    }
     const int64_t m = h->m;
     rowptr[0] = 0;
     for (int64_t x = 0; x < m; ++x) rowptr[x + 1] = rowptr[x] + h->rownnz[x];

@@ -82,6 +82,12 @@ struct cbm_handle {
     mutable float* d_scratch = nullptr;  // num_slots x scratch_k floats, sized on first use
     mutable int64_t scratch_k = 0;
 
+    // ---- column-blocked handle: the format itself lives in `inner`, built on the B m part-rows ----
+    int32_t blocks = 1;
+    cbm_handle* inner = nullptr;          // owned
+    mutable float* d_partial = nullptr;   // B m x partial_k floats: the part-rows' sums, sized on first use
+    mutable int64_t partial_k = 0;
+
     // ---- per-launch profiling ----------------------------------------------------
     bool profiling = false;
     mutable std::vector<cbm_launch_record> prof_records;
@@ -108,6 +114,10 @@ cbm_status cbm_device_candidates(int device, int64_t m, int64_t n, const int64_t
                                  std::vector<int32_t>* out_w);
 // grow the handle's split-row scratch to k columns (no-op when it is wide enough or no row is split)
 cbm_status cbm_reserve_scratch(const cbm_handle* h, int32_t k);
+// Delta lists (Eq. (2)) of every tree edge on the GPU: nplus / nminus / dptr / dcol exactly as the host merge writes them.
+cbm_status cbm_device_deltas(int device, int64_t m, const int64_t* rowptr, const int32_t* colidx, const int32_t* parent,
+                             std::vector<int32_t>* nplus, std::vector<int32_t>* nminus, std::vector<int64_t>* dptr,
+                             std::vector<uint32_t>* dcol);
 cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
                               CbmEpilogue epi, float self_weight, void* stream, bool static_scratch = false);
 size_t cbm_static_scratch_bytes();

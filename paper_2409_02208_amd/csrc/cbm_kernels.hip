@@ -484,6 +484,13 @@ struct ProfScope {
 }  // namespace
 
 cbm_status cbm_upload(cbm_handle* h) {
+    if (h->blocks > 1) {  // the format lives in the inner handle
+        const cbm_status st = cbm_upload(h->inner);
+        if (st != CBM_OK) return st;
+        h->device = h->inner->device;
+        h->on_device = true;
+        return CBM_OK;
+    }
     int dev = h->opts.device;
     int cur = -1;
     HIP_TRY(hipGetDevice(&cur), CBM_ERR_HIP);
@@ -539,6 +546,9 @@ cbm_status cbm_upload(cbm_handle* h) {
 }
 
 void cbm_release_device(cbm_handle* h) {
+    if (h->d_partial) hipFree(h->d_partial);
+    h->d_partial = nullptr;
+    h->partial_k = 0;
     for (void* e : h->prof_events) hipEventDestroy((hipEvent_t)e);
     h->prof_events.clear();
     if (h->d_tasks) hipFree(h->d_tasks);
@@ -563,6 +573,16 @@ void cbm_release_device(cbm_handle* h) {
 // Make the handle's split-row scratch at least num_slots x k floats (rounded up to four columns).
 cbm_status cbm_reserve_scratch(const cbm_handle* h, int32_t k) {
     const int64_t ld_scratch = ((int64_t)k + 3) & ~(int64_t)3;
+    if (h->blocks > 1) {  // the partial rows of the B m part-rows, and whatever the inner format needs
+        if (h->partial_k < ld_scratch) {
+            if (h->d_partial) hipFree(h->d_partial);
+            h->d_partial = nullptr;
+            h->partial_k = 0;
+            HIP_TRY(hipMalloc((void**)&h->d_partial, (size_t)h->blocks * h->m * ld_scratch * sizeof(float) + 16), CBM_ERR_ALLOC);
+            h->partial_k = ld_scratch;
+        }
+        return cbm_reserve_scratch(h->inner, k);
+    }
     if (h->num_slots <= 0 || h->scratch_k >= ld_scratch) return CBM_OK;
     // hipFree waits for the device: no product enqueued earlier is still reading the old array when it goes
     if (h->d_scratch) hipFree(h->d_scratch);
@@ -573,6 +593,88 @@ cbm_status cbm_reserve_scratch(const cbm_handle* h, int32_t k) {
     return CBM_OK;
 }
 
+namespace {
+// Column-blocked handle: Y[i,:] = sum over the B column ranges of the partial row of part-row b m + i
+// (+ self_w X[i,:], then ReLU): B loads in flight per element, added in block order.
+template <bool VEC>
+__global__ __launch_bounds__(256) void cbm_block_sum_kernel(int64_t m, int blocks, const float* __restrict__ P, int64_t ldp,
+                                                            const float* __restrict__ X, int64_t ldx, float* __restrict__ Y,
+                                                            int64_t ldy, float self_w, int relu, int k) {
+    constexpr int W = VEC ? 4 : 1;
+    const int per_row = (k + W - 1) / W;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= m * per_row) return;
+    const int64_t i = idx / per_row;
+    const int c = (int)(idx % per_row) * W;
+    float acc[W];
+#pragma unroll
+    for (int j = 0; j < W; ++j) acc[j] = 0.0f;
+    for (int b0 = 0; b0 < blocks; b0 += 8) {
+        float part[8][W];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool on = b0 + u < blocks;
+            const float* src = P + ((int64_t)(on ? b0 + u : b0) * m + i) * ldp + c;
+            if (VEC) {
+                const float4a t = __builtin_nontemporal_load(reinterpret_cast<const float4a*>(src));
+#pragma unroll
+                for (int j = 0; j < W; ++j) part[u][j] = on ? t[j] : 0.0f;
+            } else {
+                part[u][0] = on ? __builtin_nontemporal_load(src) : 0.0f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int j = 0; j < W; ++j) acc[j] += part[u][j];
+    }
+#pragma unroll
+    for (int j = 0; j < W; ++j) {
+        if (self_w != 0.0f) acc[j] = fmaf(self_w, X[i * ldx + c + j], acc[j]);
+        if (relu) acc[j] = fmaxf(acc[j], 0.0f);
+    }
+    if (VEC) {
+        float4a t;
+#pragma unroll
+        for (int j = 0; j < W; ++j) t[j] = acc[j];
+        *reinterpret_cast<float4a*>(Y + i * ldy + c) = t;
+    } else {
+        Y[i * ldy + c] = acc[0];
+    }
+}
+
+cbm_status launch_blocked(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy, CbmEpilogue epi,
+                          float self_weight, hipStream_t stream) {
+    if (const cbm_status st = cbm_reserve_scratch(h, k); st != CBM_OK) return st;
+    const int64_t ldp = h->partial_k;
+    // the part-rows carry column weights and row weight (the row weight distributes over the sum of the parts); ReLU and
+    // the self term have to wait for the whole row
+    const CbmEpilogue inner_epi = epi == CBM_EPI_ROWSCALE_RELU ? CBM_EPI_ROWSCALE : epi == CBM_EPI_SELF ? CBM_EPI_NONE : epi;
+    if (const cbm_status st = cbm_launch_product(h->inner, X, ldx, k, h->d_partial, ldp, inner_epi, 0.0f, stream, false); st != CBM_OK)
+        return st;
+    const bool vec = k % 4 == 0 && ldy % 4 == 0 && ((uintptr_t)Y & 15) == 0;
+    const int64_t threads = h->m * (vec ? k / 4 : k);
+    if (threads > 0) {
+        cbm_launch_record rec{};
+        rec.kind = 4;
+        rec.tasks = h->m;
+        rec.algorithmic_bytes = 0;  // the partial rows are this variant's overhead
+        ProfScope ps(h->inner, stream, rec);
+        const dim3 grid((unsigned)((threads + 255) / 256));
+        const float sw = epi == CBM_EPI_SELF ? self_weight : 0.0f;
+        const int relu = epi == CBM_EPI_ROWSCALE_RELU;
+        if (vec)
+            hipLaunchKernelGGL(cbm_block_sum_kernel<true>, grid, dim3(256), 0, stream, h->m, (int)h->blocks, h->d_partial, ldp, X, ldx,
+                               Y, ldy, sw, relu, (int)k);
+        else
+            hipLaunchKernelGGL(cbm_block_sum_kernel<false>, grid, dim3(256), 0, stream, h->m, (int)h->blocks, h->d_partial, ldp, X,
+                               ldx, Y, ldy, sw, relu, (int)k);
+    }
+    HIP_TRY(hipGetLastError(), CBM_ERR_HIP);
+    return CBM_OK;
+}
+}  // namespace
+
 size_t cbm_static_scratch_bytes() { return (size_t)CBM_STATIC_SCRATCH_FLOATS * sizeof(float); }
 
 cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, int32_t k, float* Y, int64_t ldy,
@@ -581,6 +683,13 @@ cbm_status cbm_launch_product(const cbm_handle* h, const float* X, int64_t ldx, 
     int cur = -1;
     HIP_TRY(hipGetDevice(&cur), CBM_ERR_HIP);
     if (cur != h->device) return CBM_ERR_STATE;  // the caller's current device must be the handle's
+    if (h->blocks > 1) {
+        if (static_scratch) {
+            cbm_set_error_detail("cbm_spmm_noalloc", "a column-blocked handle keeps B partial rows per row: more than the static scratch is for");
+            return CBM_ERR_UNSUPPORTED;
+        }
+        return launch_blocked(h, X, ldx, k, Y, ldy, epi, self_weight, stream);
+    }
 
     const int64_t ld_scratch = ((int64_t)k + 3) & ~(int64_t)3;
     float* scratch = nullptr;

@@ -227,6 +227,47 @@ def test_error_paths_return_status_codes():
     assert lib.cbm_spmm(h.ptr, 16, 2, 4, 32, 4, None) == 1
 
 
+@pytest.mark.parametrize("blocks", [2, 3, 8])
+def test_column_blocked_format_round_trips_and_keeps_property_1(blocks):
+    """Column-blocked CBM (one tree over the B m part-rows): decompression gives back the matrix (Eq. (2)), the delta
+    count stays within nnz (Property 1 holds for the stacked matrix, whose non-zeros are those of A), the tree covers
+    B m part-rows, and an option that cannot be combined is refused."""
+    g = wl.make_graph("protein", n=1500, knn=30)
+    for self_loops in (False, True):
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=self_loops, alpha=1, max_depth=16, host_only=True,
+                          column_blocks=blocks)
+        s = cbm.cbm_stats(h)
+        assert s["column_blocks"] == blocks and s["m"] == g.n
+        rows = orc.adjacency_lists(g.n, g.rowptr, g.colidx, add_self_loops=self_loops)
+        want_rp, want_ci = _csr([sorted(r) for r in rows[1:]])
+        rp, ci = cbm.cbm_decompress(h)
+        assert np.array_equal(rp, want_rp) and np.array_equal(ci, want_ci)
+        assert s["nnz"] == int(want_rp[-1])
+        assert s["num_delta_plus"] + s["num_delta_minus"] <= s["nnz"]
+        t = cbm.cbm_get_tree(h)
+        assert len(t["parent"]) == blocks * g.n
+        assert s["num_roots"] == int((t["parent"] < 0).sum())
+        # a part-row is only ever compressed against a part-row of the same column range
+        x = np.flatnonzero(t["parent"] >= 0)
+        assert np.array_equal(x // g.n, t["parent"][x] // g.n)
+    h1 = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=1, max_depth=16, host_only=True)
+    hb = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=1, max_depth=16, host_only=True, column_blocks=blocks)
+    s1, sb = cbm.cbm_stats(h1), cbm.cbm_stats(hb)
+    assert s1["column_blocks"] == 1
+    print(blocks, (sb["num_delta_plus"] + sb["num_delta_minus"]) / sb["nnz"], (s1["num_delta_plus"] + s1["num_delta_minus"]) / s1["nnz"])
+    with pytest.raises(cbm.CbmError) as e:
+        cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, host_only=True, column_blocks=blocks, transpose=True)
+    assert e.value.status == 1
+    with pytest.raises(cbm.CbmError) as e:
+        cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, host_only=True, column_blocks=-2)
+    assert e.value.status == 1
+    # rectangular, with empty rows and an empty block
+    rowptr, colidx = _csr([[0, 1, 2, 90], [], [1, 2, 90], [5]])
+    h = cbm.cbm_build(4, 100, rowptr, colidx, host_only=True, max_depth=16, column_blocks=4)
+    rp, ci = cbm.cbm_decompress(h)
+    assert np.array_equal(rp, rowptr) and np.array_equal(ci, colidx)
+
+
 def test_tuning_knobs_from_the_environment_are_held_in_range(monkeypatch):
     """Out-of-range values of the builder's environment knobs must not reach the work lists: zero sub-ranges
     would divide by zero, and an entry count of 2^24 or more would spill into a work item's flag bits."""

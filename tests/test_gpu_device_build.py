@@ -1,6 +1,6 @@
-"""The builder's candidate search on the GPU (CBM_FLAG_DEVICE_BUILD) against the host search: both follow
-one selection rule with one tie-break, so the compression tree, the delta counts and the products must be
-identical, not merely equivalent."""
+"""The builder's GPU side (CBM_FLAG_DEVICE_BUILD: candidate search and delta lists on the GPU) against the host
+builder: both follow one selection rule with one tie-break and write the delta lists in one order, so the
+compression tree, the delta lists and the products must be identical, not merely equivalent."""
 import numpy as np
 import pytest
 
@@ -42,8 +42,11 @@ def _same_tree(cbm, m, n, rowptr, colidx, **opts):
     for key in ("parent", "nplus", "nminus", "level"):
         assert np.array_equal(th[key], td[key]), (key, opts)
     sh, sd = cbm.cbm_stats(hh), cbm.cbm_stats(hd)
-    for key in ("num_delta_plus", "num_delta_minus", "depth", "rounds", "num_tasks"):
+    for key in ("num_delta_plus", "num_delta_minus", "depth", "rounds", "num_tasks", "scalar_ops", "bytes_cbm"):
         assert sh[key] == sd[key], (key, opts)
+    # the delta lists made on the GPU rebuild the matrix (Eq. (2)) exactly as the host's do
+    (rph, cih), (rpd, cid) = cbm.cbm_decompress(hh), cbm.cbm_decompress(hd)
+    assert np.array_equal(rph, rpd) and np.array_equal(cih, cid)
     return hh, hd
 
 
@@ -90,6 +93,31 @@ def test_device_candidates_on_degenerate_inputs(env):
     _same_tree(cbm, 1, 5, *_csr([[1, 3]]), max_depth=16)
     h = cbm.cbm_build(0, 5, np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32), device_build=True)
     assert cbm.cbm_stats(h)["m"] == 0
+
+
+def test_device_deltas_of_a_transposed_directed_matrix(env):
+    torch, cbm = env
+    rng = np.random.default_rng(9)
+    m, n = 4000, 2500
+    base = [sorted(rng.choice(n, size=int(s), replace=False).tolist()) for s in rng.integers(5, 60, size=200)]
+    rows = []
+    for i in range(m):   # near-copies of a few base rows: a deep tree with both kinds of delta
+        r = set(base[int(rng.integers(len(base)))])
+        r ^= set(rng.choice(n, size=3, replace=False).tolist())
+        rows.append(sorted(r))
+    rowptr, colidx = _csr(rows)
+    for opts in (dict(max_depth=16), dict(max_depth=-1, transpose=True), dict(max_depth=16, alpha=2, transpose=True)):
+        hh, hd = _same_tree(cbm, m, n, rowptr, colidx, **opts)
+        s = cbm.cbm_stats(hd)
+        assert s["num_delta_minus"] > 0 and s["depth"] > 2
+        mm, nn = (n, m) if opts.get("transpose") else (m, n)
+        X = torch.from_numpy(wl.gaussian_features(nn, 24, 3)).cuda()
+        Yh = torch.full((mm, 24), float("nan"), device="cuda")
+        Yd = torch.full((mm, 24), float("nan"), device="cuda")
+        cbm.cbm_spmm(hh, X, Yh)
+        cbm.cbm_spmm(hd, X, Yd)
+        torch.cuda.synchronize()
+        assert torch.equal(Yh, Yd)
 
 
 def test_device_build_argument_errors(env):

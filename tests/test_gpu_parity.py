@@ -406,6 +406,53 @@ def test_argument_errors_on_device_handle(env, graphs):
     assert e.value.status == 1
 
 
+@pytest.mark.parametrize("name", ["tiny", "collaboration", "protein", "rmat"])
+@pytest.mark.parametrize("blocks", [2, 8])
+def test_column_blocked_handle_gives_the_same_products(env, graphs, name, blocks):
+    """Column-blocked CBM: every product of the boundary against the oracle, as for the plain format."""
+    torch, cbm = env
+    g = graphs[name]
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=1, max_depth=16, column_blocks=blocks)
+    s = cbm.cbm_stats(h)
+    assert s["column_blocks"] == blocks
+    Xi = wl.integer_features(g.n, 16, g.meta["seed"])
+    got = _run(env, "cbm_spmm", h, Xi, g.n)
+    ref = orc.spmm_csr(g.rowptr, g.colidx, Xi) + Xi.astype(np.float64)          # the handle holds A v I
+    assert np.array_equal(got.astype(np.float64), ref)
+    d = np.diff(g.rowptr) + 1
+    for k in (3, 64, 128):
+        X = wl.gaussian_features(g.n, k, g.meta["seed"])
+        ref = orc.spmm_csr_normalized(g.rowptr, g.colidx, X)
+        assert row_scaled_error(_run(env, "cbm_spmm_normalized", h, X, g.n), ref) <= TOL
+        assert row_scaled_error(_run(env, "cbm_spmm_normalized_relu", h, X, g.n), np.maximum(ref, 0.0), scale_from=ref) <= TOL
+        mean = (orc.spmm_csr(g.rowptr, g.colidx, X) + X.astype(np.float64)) / d[:, None]
+        assert row_scaled_error(_run(env, "cbm_spmm_mean", h, X, g.n), mean) <= TOL
+        Xd = torch.from_numpy(X).cuda()
+        Y = torch.full((g.n, k), float("nan"), device="cuda")
+        cbm.cbm_spmm_gin(h, 0.25, Xd, Y)
+        torch.cuda.synchronize()
+        gin = orc.spmm_csr(g.rowptr, g.colidx, X) + 2.25 * X.astype(np.float64)   # (A v I) X + 1.25 X
+        scale = orc.spmm_csr(g.rowptr, g.colidx, np.abs(X)) + 2.25 * np.abs(X).astype(np.float64)
+        assert np.all(np.abs(Y.cpu().numpy() - gin) <= 1e-5 * scale)
+    # the GCN driver and the per-launch records go through the same handle
+    f_in, hidden, f_out = 32, 16, 8
+    X = wl.gaussian_features(g.n, f_in, 3)
+    W0, W1 = wl.glorot_uniform(f_in, hidden, 1), wl.glorot_uniform(hidden, f_out, 2)
+    out = torch.full((g.n, f_out), float("nan"), device="cuda")
+    ws = torch.empty(cbm.cbm_gcn2_workspace_bytes(h, f_in, hidden, f_out), dtype=torch.uint8, device="cuda")
+    cbm.cbm_gcn2_forward(h, *(torch.from_numpy(a).cuda() for a in (X, W0, W1)), out, ws)
+    torch.cuda.synchronize()
+    assert row_scaled_error(out.cpu().numpy(), orc.gcn2(g.rowptr, g.colidx, X, W0, W1)) <= TOL
+    cbm.cbm_profile_enable(h, True)
+    _run(env, "cbm_spmm_normalized", h, wl.gaussian_features(g.n, 8, 1), g.n)
+    recs = cbm.cbm_profile_read(h)
+    cbm.cbm_profile_enable(h, False)
+    assert recs[-1]["kind"] == 4 and all(r["milliseconds"] > 0 for r in recs)
+    with pytest.raises(cbm.CbmError) as e:   # the static scratch is not for B partial rows per row
+        cbm.cbm_spmm_noalloc(h, torch.zeros((g.n, 8), device="cuda"), torch.zeros((g.n, 8), device="cuda"))
+    assert e.value.status == 5
+
+
 def test_reserve_sizes_the_split_row_scratch_before_capture(env):
     # cbm_reserve instead of a first eager product: a handle WITH split rows is captured at once, and the replay is exact
     torch, cbm = env
