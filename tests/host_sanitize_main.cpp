@@ -12,6 +12,10 @@ cbm_status cbm_device_candidates(int, int64_t, int64_t, const int64_t*, const in
                                  int64_t, int32_t, std::vector<int32_t>*, std::vector<int32_t>*, std::vector<int32_t>*) {
     return CBM_ERR_STATE;
 }
+cbm_status cbm_device_deltas(int, int64_t, const int64_t*, const int32_t*, const int32_t*, std::vector<int32_t>*, std::vector<int32_t>*,
+                             std::vector<int64_t>*, std::vector<uint32_t>*) {
+    return CBM_ERR_STATE;
+}
 const char* cbm_get_error_detail() { return ""; }
 int main() {
     std::mt19937 rng(1);
@@ -38,12 +42,26 @@ int main() {
         h.opts.hub_cap = (trial % 4 == 0) ? 3 : 0;
         h.opts.num_threads = 1 + trial % 4;
         h.opts.flags = CBM_FLAG_HOST_ONLY;
+        h.opts.column_blocks = (trial % 5 == 1) ? 3 : (trial % 11 == 2) ? 64 : 0;  // column-blocked builds too
         cbm_status st = cbm_build_host(m, n, rp.data(), ci.data(), &h);
         if (st != CBM_OK) { printf("build failed %d\n", st); return 1; }
         std::vector<int64_t> orp(m + 1);
         std::vector<int32_t> oci(h.stats.nnz + 1);
         st = cbm_decompress_host(&h, orp.data(), oci.data());
         if (st != CBM_OK) { printf("decompress failed %d\n", st); return 1; }
+        if (!h.opts.add_self_loops && (orp != rp || !std::equal(ci.begin(), ci.end(), oci.begin()))) { printf("round trip differs\n"); return 1; }
+        struct Owner {  // the inner handle of a column-blocked build is heap-allocated and owned by the outer one
+            cbm_handle* p;
+            ~Owner() { delete p; }
+        } owner{h.inner};
+        if (h.inner) {  // the emitted work lists are the inner handle's: B m part-rows
+            const cbm_handle& in = *h.inner;
+            h.tasks = in.tasks;
+            h.comb = in.comb;
+            h.stream = in.stream;
+            h.num_slots = in.num_slots;
+            m = (int)in.m;
+        }
         // bounds of the emitted stream / tasks
         for (auto& t : h.tasks) {
             uint32_t len = t.len_flags & CBM_TASK_LEN_MASK;
