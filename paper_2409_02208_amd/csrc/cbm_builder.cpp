@@ -948,13 +948,20 @@ cbm_status Builder::emit(int32_t nrounds) {
     }
     if (at >= (int64_t)UINT32_MAX) return CBM_ERR_UNSUPPORTED;
     h->stream.resize((size_t)at);
+    // A row's deltas go into the stream in ONE ascending sweep over the columns (Delta+ and Delta- merged; the sign
+    // travels with the entry).  Work items that run at the same time then move through X in step, low rows first,
+    // and find each other's rows in L2: 4 to 6 % off the protein product against "Delta+ then Delta-".
+    const bool merge_sort = std::getenv("CBM_NO_MERGE_SORT") == nullptr;
     // Pass 2, on all threads: the entries themselves.  A path is its rows' deltas, each followed by the row's marker;
     // a split row is its deltas re-sorted by column.
     parallel_chunks(nthreads, (int64_t)paths.size(), 256, [&](int64_t b, int64_t e, int) {
         for (int64_t i = b; i < e; ++i) {
             uint32_t* out = h->stream.data() + paths[i].base;
             for (int32_t v = paths[i].x; v >= 0; v = next[v]) {
+                uint32_t* first = out;
                 out = std::copy(h->dcol.begin() + h->dptr[v], h->dcol.begin() + h->dptr[v + 1], out);
+                if (merge_sort && h->nminus[v] > 0)
+                    std::sort(first, out, [](uint32_t a, uint32_t b2) { return (a & CBM_ENTRY_INDEX_MASK) < (b2 & CBM_ENTRY_INDEX_MASK); });
                 *out++ = (uint32_t)v | CBM_ENTRY_MARK | (internal[v] ? CBM_ENTRY_INTERNAL : 0u);
             }
         }
