@@ -499,7 +499,10 @@ def test_gcn2_rejects_overlapping_buffers(env, graphs):
 
 
 @pytest.mark.parametrize("M,N,K", [(1000, 64, 500), (777, 3, 64), (513, 112, 256), (256, 256, 256), (130, 33, 7),
-                                   (1, 1, 1), (300, 200, 37)])
+                                   (1, 1, 1), (300, 200, 37),
+                                   # widths served by the 16-column tiles (N mod 32 in 1..16 above 32), ragged M and K too
+                                   (2000, 112, 256), (1029, 100, 61), (515, 48, 128), (640, 40, 36), (300, 80, 500),
+                                   (129, 65, 33), (4100, 97, 5)])
 def test_dense_matmul(env, M, N, K):
     torch, cbm = env
     rng = np.random.default_rng(M + N + K)
