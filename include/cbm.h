@@ -147,7 +147,8 @@ typedef struct {
                                 B m part-rows; num_roots, num_internal, depth and the
                                 delta counts are those of the part-rows, and scalar_ops
                                 includes the (B - 1) m additions of the block sum        */
-    int32_t reserved_;
+    int32_t bundled_rounds;  /* rounds whose paths are gathered in one sweep per path
+                                (long work items of more than one row)                 */
 } cbm_stats_t;
 
 /*

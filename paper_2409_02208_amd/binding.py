@@ -47,7 +47,7 @@ class cbm_stats_t(C.Structure):
                 ("scalar_ops", C.c_int64), ("num_tasks", C.c_int64), ("num_split_rows", C.c_int64),
                 ("bytes_csr", C.c_int64), ("bytes_cbm", C.c_int64), ("depth", C.c_int32), ("alpha", C.c_int32),
                 ("add_self_loops", C.c_int32), ("rounds", C.c_int32), ("build_seconds", C.c_double),
-                ("column_blocks", C.c_int32), ("reserved_", C.c_int32)]
+                ("column_blocks", C.c_int32), ("bundled_rounds", C.c_int32)]
 
     def as_dict(self) -> dict:
         return {f: getattr(self, f) for f, _ in self._fields_}

@@ -28,6 +28,12 @@ constexpr uint32_t CBM_DELTA_MINUS = 0x80000000u;
 constexpr uint32_t CBM_ENTRY_MARK = 0x40000000u;      // entry stores a row instead of gathering one
 constexpr uint32_t CBM_ENTRY_INTERNAL = 0x20000000u;  // marker: another work item reads this row, keep it unscaled
 constexpr uint32_t CBM_ENTRY_INDEX_MASK = 0x1fffffffu;
+// Bundled paths: the rows of a path are taken in groups of CBM_BUNDLE_ROWS, and a group's deltas come in ONE ascending
+// sweep over the columns, each entry saying in bits 26-28 which row of the group it belongs to; the group's markers
+// follow, tagged alike, in row order.  Rows and columns are limited to 26 bits in a handle that bundles.
+constexpr uint32_t CBM_BUNDLE_SLOT_SHIFT = 26;
+constexpr uint32_t CBM_BUNDLE_INDEX_MASK = 0x03ffffffu;
+constexpr int32_t CBM_BUNDLE_ROWS = 4;  // most rows in a bundled path (a power of two)
 constexpr int CBM_XCD = 8;  // accelerator complex dies of an MI355X; workgroup (linear id) b runs on XCD b mod 8
 
 struct CbmLevel {
@@ -39,6 +45,7 @@ struct CbmLevel {
     int64_t rows_written = 0;                      // matrix rows written by the main launch
     int64_t comb_segments = 0;                     // scratch rows read by the combine launch
     int64_t comb_parent_reads = 0;
+    bool bundled = false;                          // the round's paths are emitted as bundles (see CBM_BUNDLE_SLOT_SHIFT)
     // work items in locality order, cut into one contiguous block per XCD (absolute indices into tasks[])
     bool by_xcd = false;
     int64_t xcd_begin[CBM_XCD] = {}, xcd_count[CBM_XCD] = {};
@@ -67,6 +74,7 @@ struct cbm_handle {
     int64_t num_slots = 0;         // scratch rows needed by split rows
     int64_t seg_begin[CBM_XCD] = {}, seg_count[CBM_XCD] = {};  // segment work items in tasks[], per column range
     int64_t seg_deltas = 0;        // delta entries gathered by the segment launch
+    bool bundled = false;          // some round's paths are emitted as bundles: delta columns are 26-bit in this handle
     cbm_stats_t stats{};
 
     // ---- device arrays (owned) ---------------------------------------------------

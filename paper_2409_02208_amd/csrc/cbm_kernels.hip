@@ -283,6 +283,165 @@ __global__ __launch_bounds__(256, level_min_waves(RAGGED, LANES, MODE, UMAX)) vo
         st_row<RAGGED, LANES>(scratch + (int64_t)tk.row * ld_scratch, c0, k, acc);
 }
 
+// Bundled paths.  The rows r_1 -> r_2 -> ... of a path are compressed against one another, so
+//     Y[r_j,:] = Y[parent,:] + sum_{i <= j} ( sum_{Delta+(r_i)} X - sum_{Delta-(r_i)} X ).
+// The kernel above walks them row by row: three or four short sweeps over the columns per work item, and work items at
+// different rows of their paths ask for unrelated parts of X (26-34 % L2 hits against 71 % for a round of rows stored
+// in full, which are one long sweep each).  Here ALL deltas of a path of at most CBM_BUNDLE_ROWS rows come in one
+// ascending sweep, each tagged with the row it belongs to; the group keeps one partial sum per row and, when the deltas
+// are done, forms the running sums and stores the rows (the path's markers follow its deltas in the stream).  Work
+// items that start together then move through X together.  The sweep itself is a plain loop: no markers inside it.
+constexpr int bundle_min_waves(bool ragged, int lanes, int mode, int umax) { return umax >= 8 ? (ragged ? 3 : 4) : 6; }
+
+template <bool RAGGED, int LANES, int MODE, int UMAX>
+__global__ __launch_bounds__(256, bundle_min_waves(RAGGED, LANES, MODE, UMAX)) void cbm_bundle_kernel(
+    const CbmTask* __restrict__ tasks, int64_t ntasks, const CbmSegMap map, const uint32_t* __restrict__ stream,
+    const float* __restrict__ X, int64_t ldx, float* Y, int64_t ldy, const float* __restrict__ ws, const float* __restrict__ rw,
+    float self_w, int k) {
+    using M = Mode<MODE>;
+    constexpr int G = 64 / LANES;
+    constexpr int U = LANES < UMAX ? LANES : UMAX;
+    constexpr int BPC = LANES / U;
+    constexpr int R = CBM_BUNDLE_ROWS;
+    static_assert(R == 4, "the choice among the partial sums below is written for four rows");
+    const int lane = threadIdx.x & 63;
+    const int sub = lane / LANES;
+    const int sl = lane % LANES;
+    int64_t t;
+    if (map.use) {
+        const int xcd = blockIdx.x % CBM_XCD;
+        const int64_t tl = ((int64_t)(blockIdx.x / CBM_XCD) * 4 + (threadIdx.x >> 6)) * G + sub;
+        if (tl >= map.count[xcd]) return;
+        t = map.begin[xcd] + tl;
+    } else {
+        t = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * G + sub;
+        if (t >= ntasks) return;
+    }
+    const CbmTask tk = tasks[t];
+    const uint32_t total = tk.len_flags & CBM_TASK_LEN_MASK;
+    // the last entries are the markers of the path's rows, in row order (1 .. R of them: the builder guarantees it)
+    uint32_t nrows = 0;
+#pragma unroll
+    for (int s = 1; s <= R; ++s)
+        if ((uint32_t)s <= total && (stream[tk.start + total - s] & CBM_ENTRY_MARK)) nrows = (uint32_t)s;
+        else break;
+    const uint32_t len = total - nrows;  // the deltas
+    const int c0 = first_column<RAGGED, LANES>(blockIdx.y, sl);
+    const bool colok = c0 < k;
+
+    Vec4 run;  // the parent's row: the running sum starts there
+#pragma unroll
+    for (int c = 0; c < 4; ++c) run.v[c] = 0.0f;
+    if (tk.parent >= 0 && colok) run = ld_row<RAGGED, LANES>(Y + (int64_t)tk.parent * ldy, c0, k);
+    Vec4 acc[R];  // the partial sum of each row's own deltas
+#pragma unroll
+    for (int s = 0; s < R; ++s)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[s].v[c] = 0.0f;
+
+    const uint32_t* es = stream + tk.start;
+    const float* wes = ws + tk.start;
+    auto load_e = [&](int chunk) -> uint32_t {
+        const uint32_t idx = (uint32_t)chunk * LANES + sl;
+        return idx < len ? __builtin_nontemporal_load(es + idx) : 0u;
+    };
+    auto load_w = [&](uint32_t e, int chunk) -> float {  // what the gathered row is multiplied by: +-d_j^-1/2, or +-1
+        const uint32_t idx = (uint32_t)chunk * LANES + sl;
+        if (idx >= len) return 0.0f;
+        if (M::wcol) return __builtin_nontemporal_load(wes + idx);
+        return __uint_as_float(0x3f800000u | (e & CBM_DELTA_MINUS));  // the fused multiply-add is then an exact add or subtract
+    };
+    uint32_t e0 = load_e(0), e1 = load_e(1), e2 = load_e(2);
+    float w0 = load_w(e0, 0), w1 = load_w(e1, 1);
+    float wprev = 0.0f;
+    int cur = 0;
+
+    struct Batch {
+        Vec4 x[U];
+        uint32_t e[U];
+    };
+    const int nb = (int)((len + U - 1) / U);
+    auto fetch = [&](Batch& S, int b) {
+        if (b > 0 && b % BPC == 0) {
+            const int chunk = b / BPC;
+            e0 = e1;
+            wprev = w0;
+            w0 = w1;
+            e1 = e2;
+            e2 = load_e(chunk + 2);
+            w1 = load_w(e1, chunk + 1);
+            cur = chunk;
+        }
+        const int off = (b % BPC) * U;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            S.e[u] = (uint32_t)__shfl((int)e0, off + u, LANES);
+            if ((uint32_t)(b * U + u) < len && colok) {
+                S.x[u] = ld_row<RAGGED, LANES>(X + (int64_t)(S.e[u] & CBM_BUNDLE_INDEX_MASK) * ldx, c0, k);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) S.x[u].v[c] = 0.0f;
+            }
+        }
+    };
+    auto consume = [&](const Batch& S, int b) {
+        const float wsrc = (b / BPC == cur) ? w0 : wprev;
+        const int off = (b % BPC) * U;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float w = __shfl(wsrc, off + u, LANES);  // (0 past the end of the deltas, where the row is zero too)
+            const uint32_t slot = (S.e[u] >> CBM_BUNDLE_SLOT_SHIFT) & (uint32_t)(R - 1);  // the same for the whole group
+            auto add = [&](Vec4& a) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) a.v[c] = fmaf(w, S.x[u].v[c], a.v[c]);
+            };
+            if (slot & 2u) { if (slot & 1u) add(acc[3]); else add(acc[2]); }
+            else { if (slot & 1u) add(acc[1]); else add(acc[0]); }
+        }
+    };
+    Batch A, B;
+    if (nb > 0) fetch(A, 0);
+    for (int b = 0; b < nb; b += 2) {
+        if (b + 1 < nb) fetch(B, b + 1);
+        consume(A, b);
+        if (b + 2 < nb) fetch(A, b + 2);
+        if (b + 1 < nb) consume(B, b + 1);
+    }
+    // the rows of the path, in order: running sum, then the store its marker asks for
+    uint32_t em[R];
+    float wm[R];
+    Vec4 own[R];
+#pragma unroll
+    for (int s = 0; s < R; ++s) {  // everything the stores need, in flight together
+        em[s] = 0u;
+        wm[s] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) own[s].v[c] = 0.0f;
+        if ((uint32_t)s < nrows) {
+            em[s] = es[len + s];
+            if (M::wcol) wm[s] = wes[len + s];
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < R; ++s) {
+        if ((uint32_t)s < nrows) {
+            const uint32_t row = em[s] & CBM_ENTRY_INDEX_MASK;
+            if (!M::wcol && M::wrow) wm[s] = rw[row];
+            if (M::self && !(em[s] & CBM_ENTRY_INTERNAL) && colok) own[s] = ld_row<RAGGED, LANES>(X + (int64_t)row * ldx, c0, k);
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < R; ++s) {
+        if ((uint32_t)s < nrows) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) run.v[c] += acc[s].v[c];
+            if (colok)
+                store_row<RAGGED, LANES, MODE>(Y + (int64_t)(em[s] & CBM_ENTRY_INDEX_MASK) * ldy, c0, k, run,
+                                               !(em[s] & CBM_ENTRY_INTERNAL), wm[s], own[s], self_w);
+        }
+    }
+}
+
 // Rows whose delta list was cut into segments: Y[x,:] = Y[r_x,:] + sum of the row's segment sums.
 template <bool RAGGED, int LANES, int MODE>
 __global__ __launch_bounds__(256) void cbm_combine_kernel(const CbmTask* __restrict__ comb, int64_t ncomb,
@@ -349,11 +508,12 @@ __global__ __launch_bounds__(256) void cbm_finish_kernel(const int32_t* __restri
 // marker of row x.  Stored once per handle so that the product kernel reads weights as it reads entries --
 // coalesced -- instead of gathering one word per delta.
 __global__ __launch_bounds__(256) void cbm_entry_weights_kernel(const uint32_t* __restrict__ stream, int64_t nent,
-                                                                const float* __restrict__ dinv, float* __restrict__ w) {
+                                                                const float* __restrict__ dinv, float* __restrict__ w,
+                                                                uint32_t delta_mask) {  // 26 bits in a handle that bundles
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= nent) return;
     const uint32_t e = stream[i];
-    const float d = dinv[e & CBM_ENTRY_INDEX_MASK];
+    const float d = dinv[e & ((e & CBM_ENTRY_MARK) ? CBM_ENTRY_INDEX_MASK : delta_mask)];
     w[i] = (!(e & CBM_ENTRY_MARK) && (e & CBM_DELTA_MINUS)) ? -d : d;
 }
 
@@ -376,11 +536,35 @@ struct LaunchCtx {
 };
 
 template <bool RAGGED, int LANES, int MODE, int UMAX>
+void launch_bundles(const LaunchCtx& c, const CbmLevel& L) {
+    constexpr int G = 64 / LANES;
+    const int ychunks = (c.k + LANES * 4 - 1) / (LANES * 4);
+    CbmSegMap map{};
+    if (L.by_xcd) {
+        int64_t most = 0;
+        for (int j = 0; j < CBM_XCD; ++j) {
+            map.begin[j] = L.xcd_begin[j];
+            map.count[j] = L.xcd_count[j];
+            most = std::max(most, map.count[j]);
+        }
+        map.use = 1;
+        dim3 grid((unsigned)(CBM_XCD * ((most + 4 * G - 1) / (4 * G))), (unsigned)ychunks);
+        hipLaunchKernelGGL((cbm_bundle_kernel<RAGGED, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream, c.h->d_tasks,
+                           (int64_t)c.h->tasks.size(), map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.ws, c.rw, c.self_w, c.k);
+        return;
+    }
+    dim3 grid((unsigned)((L.task_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
+    hipLaunchKernelGGL((cbm_bundle_kernel<RAGGED, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream, c.h->d_tasks + L.task_begin,
+                       L.task_count, map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.ws, c.rw, c.self_w, c.k);
+}
+
+template <bool RAGGED, int LANES, int MODE, int UMAX>
 void launch_level(const LaunchCtx& c, const CbmLevel& L) {
     constexpr int G = 64 / LANES;
     const int ychunks = (c.k + LANES * 4 - 1) / (LANES * 4);
     CbmSegMap map{};
     if (L.task_count <= 0) return;
+    if (L.bundled) return launch_bundles<RAGGED, LANES, MODE, UMAX>(c, L);
     if (L.by_xcd) {  // one block of the (locality-ordered) work items per XCD
         int64_t most = 0;
         for (int j = 0; j < CBM_XCD; ++j) {
@@ -521,7 +705,7 @@ cbm_status cbm_upload(cbm_handle* h) {
         hipError_t e = hipMalloc((void**)&h->d_wstream, nent * sizeof(float));
         if (e == hipSuccess) {
             hipLaunchKernelGGL(cbm_entry_weights_kernel, dim3((unsigned)((nent + 255) / 256)), dim3(256), 0, 0, h->d_stream,
-                               nent, h->d_dinv, h->d_wstream);
+                               nent, h->d_dinv, h->d_wstream, h->bundled ? CBM_BUNDLE_INDEX_MASK : CBM_ENTRY_INDEX_MASK);
             e = hipGetLastError();
             if (e == hipSuccess) e = hipDeviceSynchronize();
         }

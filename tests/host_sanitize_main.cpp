@@ -69,11 +69,28 @@ int main() {
             if (t.parent >= m) { printf("bad parent\n"); return 1; }
             for (uint32_t i = 0; i < len; ++i) {
                 uint32_t e = h.stream[t.start + i];
-                uint32_t idx = e & CBM_ENTRY_INDEX_MASK;
+                const bool bundled = h.inner ? h.inner->bundled : h.bundled;  // then delta columns are 26-bit, with row tags above
+                uint32_t idx = e & ((e & CBM_ENTRY_MARK) || !bundled ? CBM_ENTRY_INDEX_MASK : CBM_BUNDLE_INDEX_MASK);
                 if (e & CBM_ENTRY_MARK) { if ((int64_t)idx >= m) { printf("marker row out of range\n"); return 1; } }
                 else if ((int64_t)idx >= n) { printf("column out of range\n"); return 1; }
             }
             if ((t.len_flags & CBM_TASK_SEGMENT) && t.row >= h.num_slots) { printf("slot out of range\n"); return 1; }
+        }
+        // a bundled round: every path has its deltas first (row tags within the limit), then at most CBM_BUNDLE_ROWS markers
+        for (auto& L : (h.inner ? h.inner->levels : h.levels)) {
+            if (!L.bundled) continue;
+            for (int64_t ti = L.task_begin; ti < L.task_begin + L.task_count; ++ti) {
+                const CbmTask& t = h.tasks[ti];
+                uint32_t len = t.len_flags & CBM_TASK_LEN_MASK, nmark = 0;
+                bool seen_marker = false;
+                for (uint32_t i = 0; i < len; ++i) {
+                    const uint32_t e = h.stream[t.start + i];
+                    if (e & CBM_ENTRY_MARK) { seen_marker = true; ++nmark; }
+                    else if (seen_marker) { printf("delta after a marker in a bundle\n"); return 1; }
+                    else if (((e >> CBM_BUNDLE_SLOT_SHIFT) & 7u) >= (uint32_t)CBM_BUNDLE_ROWS) { printf("row tag out of range\n"); return 1; }
+                }
+                if (nmark < 1 || nmark > (uint32_t)CBM_BUNDLE_ROWS) { printf("bundle of %u rows\n", nmark); return 1; }
+            }
         }
         for (auto& c : h.comb) if ((int64_t)c.start + (c.len_flags & CBM_TASK_LEN_MASK) > h.num_slots) { printf("comb slots\n"); return 1; }
     }

@@ -453,6 +453,49 @@ def test_column_blocked_handle_gives_the_same_products(env, graphs, name, blocks
     assert e.value.status == 5
 
 
+@pytest.mark.parametrize("name", ["collaboration", "protein", "citation"])
+def test_bundled_rounds_give_the_same_products(env, graphs, name, monkeypatch):
+    """Rounds of long multi-row paths are gathered in one sweep per path (one partial sum per row of the path): every
+    product against the oracle with bundling forced onto the reduced graphs, whose work items are too short for it
+    otherwise; aligned and ragged widths, strided operands, a depth that leaves rows for the deferred finish."""
+    torch, cbm = env
+    g = graphs[name]
+    monkeypatch.setenv("CBM_BUNDLE_MIN", "1")
+    h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=1, max_depth=16)
+    hp = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=0, max_depth=-1)
+    monkeypatch.delenv("CBM_BUNDLE_MIN")
+    s = cbm.cbm_stats(h)
+    assert s["bundled_rounds"] >= 1 and cbm.cbm_stats(hp)["bundled_rounds"] >= 1 and s["num_internal"] > 0
+    Xi = wl.integer_features(g.n, 16, g.meta["seed"])
+    assert np.array_equal(_run(env, "cbm_spmm", hp, Xi, g.n).astype(np.float64), orc.spmm_csr(g.rowptr, g.colidx, Xi))
+    d = np.diff(g.rowptr) + 1
+    for k in (3, 64, 112, 130, 256):
+        X = wl.gaussian_features(g.n, k, g.meta["seed"])
+        ref = orc.spmm_csr_normalized(g.rowptr, g.colidx, X)
+        assert row_scaled_error(_run(env, "cbm_spmm_normalized", h, X, g.n), ref) <= TOL
+        assert row_scaled_error(_run(env, "cbm_spmm_normalized_relu", h, X, g.n), np.maximum(ref, 0.0), scale_from=ref) <= TOL
+        mean = (orc.spmm_csr(g.rowptr, g.colidx, X) + X.astype(np.float64)) / d[:, None]
+        assert row_scaled_error(_run(env, "cbm_spmm_mean", h, X, g.n), mean) <= TOL
+        Xd = torch.from_numpy(X).cuda()
+        Y = torch.full((g.n, k), float("nan"), device="cuda")
+        cbm.cbm_spmm_gin(hp, 0.25, Xd, Y)
+        torch.cuda.synchronize()
+        gin = orc.spmm_csr(g.rowptr, g.colidx, X) + 1.25 * X.astype(np.float64)
+        scale = orc.spmm_csr(g.rowptr, g.colidx, np.abs(X)) + 1.25 * np.abs(X).astype(np.float64)
+        assert np.all(np.abs(Y.cpu().numpy() - gin) <= 1e-5 * scale)
+    # strided operands: column slices of wider buffers
+    Xw = torch.from_numpy(wl.gaussian_features(g.n, 96, 3)).cuda()
+    Yw = torch.full((g.n, 80), float("nan"), device="cuda")
+    cbm.cbm_spmm_normalized(h, Xw[:, 8:72], Yw[:, 4:68])
+    torch.cuda.synchronize()
+    ref = orc.spmm_csr_normalized(g.rowptr, g.colidx, Xw[:, 8:72].cpu().numpy())
+    assert row_scaled_error(Yw[:, 4:68].cpu().numpy(), ref) <= TOL
+    # the same tree without bundling gives the same integer result bit for bit, and the bundled product is repeatable
+    Y1 = _run(env, "cbm_spmm_normalized", h, wl.gaussian_features(g.n, 64, 9), g.n)
+    Y2 = _run(env, "cbm_spmm_normalized", h, wl.gaussian_features(g.n, 64, 9), g.n)
+    assert np.array_equal(Y1, Y2)
+
+
 def test_reserve_sizes_the_split_row_scratch_before_capture(env):
     # cbm_reserve instead of a first eager product: a handle WITH split rows is captured at once, and the replay is exact
     torch, cbm = env
