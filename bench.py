@@ -50,7 +50,8 @@ FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
 # units' vector-memory path has the same figure: 256 CUs x 64 B per clock x 2.4 GHz.
 L2_PEAK_GBS = 8 * 16 * 128 * 2.4
 COUNTER_GROUPS = (("fetch", ["FETCH_SIZE"]), ("write", ["WRITE_SIZE"]), ("l2", ["TCC_REQ_sum", "TCC_HIT_sum", "TCC_MISS_sum"]))
-KIND_NAMES = {0: "rounds of paths", 1: "segments of split rows", 2: "combine of split rows", 3: "deferred finish"}
+KIND_NAMES = {0: "rounds of paths", 1: "segments of split rows", 2: "combine of split rows", 3: "deferred finish",
+              4: "sum of column blocks"}
 
 DEFAULTS = {  # workload -> k of the timed product, alpha, GCN shape or None
     "tiny": dict(k=16, alpha=0, gcn=(16, 8, 4)),
