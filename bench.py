@@ -50,6 +50,8 @@ FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
 # units' vector-memory path has the same figure: 256 CUs x 64 B per clock x 2.4 GHz.
 L2_PEAK_GBS = 8 * 16 * 128 * 2.4
 COUNTER_GROUPS = (("fetch", ["FETCH_SIZE"]), ("write", ["WRITE_SIZE"]), ("l2", ["TCC_REQ_sum", "TCC_HIT_sum", "TCC_MISS_sum"]))
+# every kernel a product call can launch (the counter children match dispatches to the library's launch records by order)
+PRODUCT_KERNELS = ("cbm_level_kernel", "cbm_bundle_kernel", "cbm_combine_kernel", "cbm_finish_kernel", "cbm_block_sum_kernel")
 KIND_NAMES = {0: "rounds of paths", 1: "segments of split rows", 2: "combine of split rows", 3: "deferred finish",
               4: "sum of column blocks"}
 
@@ -248,7 +250,7 @@ def run_counter_children(args, cache_dir):
                 rows.setdefault(int(row["Dispatch_Id"]), dict(name=row["Kernel_Name"]))[row["Counter_Name"]] = float(row["Counter_Value"])
         disp = [rows[i] for i in sorted(rows)]
         copies = [x for x in disp if "copyBuffer" in x["name"]]
-        mine = [x for x in disp if any(s in x["name"] for s in ("cbm_level_kernel", "cbm_combine_kernel", "cbm_finish_kernel"))]
+        mine = [x for x in disp if any(s in x["name"] for s in PRODUCT_KERNELS)]
         want = sum(p["reps"] * len(p["launches"]) for p in plan["plan"])
         if len(mine) != want:
             return None, f"{len(mine)} product launches under the counters, {want} expected"
