@@ -854,7 +854,8 @@ double Builder::plan(int64_t path_max, int32_t* nrounds_out) {
 // Rounds whose work items are long (kBundleMinEntries entries on average) and hold more than one row are going to be
 // bundled; their paths are then cut again so that none has more than CBM_BUNDLE_ROWS rows.  (The rows cut off head new
 // paths one round later; emit() bundles a round only if every path in it obeys the limit, so a round that the second
-// cut changes in an unforeseen way simply stays in the plain layout.)
+// cut changes in an unforeseen way simply stays in the plain layout.)  The limit is given up if it would lengthen the
+// product by more than an eighth of its rounds.
 void Builder::choose_bundled_rounds(int64_t path_max, int32_t* nrounds) {
     std::vector<int64_t> ent(*nrounds + 1, 0), items(*nrounds + 1, 0);
     std::vector<uint8_t> multi(*nrounds + 1, 0);
@@ -870,7 +871,14 @@ void Builder::choose_bundled_rounds(int64_t path_max, int32_t* nrounds) {
     bool any = false;
     for (int r = 1; r <= *nrounds; ++r)
         if (multi[r] && ent[r] >= bundle_min * items[r]) cap_rows_in_round[r] = 1, any = true;
-    if (any) plan(path_max, nrounds);  // (the limits stay in force for every later plan() of this build)
+    if (!any) return;
+    const int32_t before = *nrounds;
+    plan(path_max, nrounds);  // (the limits stay in force for every later plan() of this build)
+    if (*nrounds > before + std::max(1, before / 8)) {
+        // a very deep tree: the row limit would add dependent launches, which cost more than the sweeps save
+        cap_rows_in_round.clear();
+        plan(path_max, nrounds);
+    }
 }
 
 // The paper prunes compression opportunities that do not pay for their overhead (Section 2.2, "Edge

@@ -13,6 +13,8 @@
 // memory (four 32-bit reads, conflict-free: a half-wave reads 32 consecutive n).
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "cbm_internal.h"
 
 namespace {
@@ -176,11 +178,12 @@ __global__ __launch_bounds__(256) void cbm_gemm_kernel(int64_t M, int N, int K, 
 // (its row stride is 16 mod 32 banks, so the four k rows a wave reads fall on disjoint halves of the banks).
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-template <int NT16, bool VEC>
+template <int NT16, int H, bool VEC>
 __global__ __launch_bounds__(256) void cbm_gemm16_kernel(int64_t M, int N, int K, const float* __restrict__ A, int64_t lda,
                                                          const float* __restrict__ B, int64_t ldb, float* __restrict__ C,
                                                          int64_t ldc) {
     constexpr int BN = 16 * NT16;
+    constexpr int BM = 64 * H;                           // a wave owns H halves of 16 rows
     constexpr int LDB_S = BN + ((NT16 & 1) ? 0 : 16);   // row stride = 16 mod 32 words
     constexpr int BUF = BM * LDA_S + BK * LDB_S;
     constexpr int BQ = BK * BN / 4;                      // float4 of the B slab
@@ -195,19 +198,19 @@ __global__ __launch_bounds__(256) void cbm_gemm16_kernel(int64_t M, int N, int K
     const int64_t row0 = (int64_t)blockIdx.x * BM;
     const int col0 = blockIdx.y * BN;
 
-    floatx4 acc[2][NT16];
+    floatx4 acc[H][NT16];
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < H; ++h)
 #pragma unroll
         for (int t = 0; t < NT16; ++t)
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[h][t][v] = 0.0f;
 
-    float4 ra[4];
+    float4 ra[2 * H];
     float4 rb[BV];
     const int a_r = tid >> 3;
     const int a_k = (tid & 7) * 4;
-    uint32_t keep_a[4][4], keep_b[BV];
+    uint32_t keep_a[2 * H][4], keep_b[BV];
     auto load4 = [&](const float* base, int64_t stride, int64_t r, int c, int cmax) -> float4 {
         float4 v;  // four consecutive elements c..c+3 of row r, from clamped (always valid) addresses
         if (VEC) {
@@ -223,7 +226,7 @@ __global__ __launch_bounds__(256) void cbm_gemm16_kernel(int64_t M, int N, int K
     };
     auto load_slab = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2 * H; ++i) {
             ra[i] = load4(A, lda, min(row0 + a_r + 32 * i, M - 1), k0 + a_k, K);
 #pragma unroll
             for (int j = 0; j < 4; ++j) keep_a[i][j] = (k0 + a_k + j < K) ? 0xffffffffu : 0u;
@@ -241,7 +244,7 @@ __global__ __launch_bounds__(256) void cbm_gemm16_kernel(int64_t M, int N, int K
         float* as = smem + buf * BUF;
         float* bs = as + BM * LDA_S;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2 * H; ++i) {
             const float4 v = make_float4(masked(ra[i].x, keep_a[i][0]), masked(ra[i].y, keep_a[i][1]),
                                          masked(ra[i].z, keep_a[i][2]), masked(ra[i].w, keep_a[i][3]));
             *reinterpret_cast<float4*>(as + (a_r + 32 * i) * LDA_S + a_k) = v;
@@ -258,7 +261,7 @@ __global__ __launch_bounds__(256) void cbm_gemm16_kernel(int64_t M, int N, int K
     };
 
     struct Frag {
-        float a[2];
+        float a[H];
         float b[NT16];
     };
     const int nslab = (K + BK - 1) / BK;
@@ -268,20 +271,19 @@ __global__ __launch_bounds__(256) void cbm_gemm16_kernel(int64_t M, int N, int K
     for (int s = 0; s < nslab; ++s) {
         const int buf = s & 1;
         if (s + 1 < nslab) load_slab((s + 1) * BK);
-        const float* as = smem + buf * BUF + (wave * 32 + l16) * LDA_S + kq;
+        const float* as = smem + buf * BUF + (wave * 16 * H + l16) * LDA_S + kq;
         const float* bs = smem + buf * BUF + BM * LDA_S + kq * LDB_S + l16;
         auto read_frag = [&](Frag& f, int k4) {
-            f.a[0] = as[k4];
-            f.a[1] = as[16 * LDA_S + k4];
+#pragma unroll
+            for (int h = 0; h < H; ++h) f.a[h] = as[h * 16 * LDA_S + k4];
 #pragma unroll
             for (int t = 0; t < NT16; ++t) f.b[t] = bs[k4 * LDB_S + t * 16];
         };
         auto mma = [&](const Frag& f) {
 #pragma unroll
-            for (int t = 0; t < NT16; ++t) {  // neighbouring MFMAs write different accumulators
-                acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a[0], f.b[t], acc[0][t], 0, 0, 0);
-                acc[1][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a[1], f.b[t], acc[1][t], 0, 0, 0);
-            }
+            for (int t = 0; t < NT16; ++t)  // neighbouring MFMAs write different accumulators
+#pragma unroll
+                for (int h = 0; h < H; ++h) acc[h][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(f.a[h], f.b[t], acc[h][t], 0, 0, 0);
         };
         Frag f0, f1;
         read_frag(f0, 0);
@@ -306,32 +308,33 @@ __global__ __launch_bounds__(256) void cbm_gemm16_kernel(int64_t M, int N, int K
         const int c = col0 + t * 16 + l16;
         if (c >= N) continue;
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < H; ++h)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int64_t r = row0 + wave * 32 + h * 16 + 4 * kq + v;
+                const int64_t r = row0 + wave * 16 * H + h * 16 + 4 * kq + v;
                 if (r < M) C[r * ldc + c] = acc[h][t][v];
             }
     }
 }
 
-template <int NT16, bool VEC>
+template <int NT16, int H, bool VEC>
 cbm_status launch16(int64_t M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
                     hipStream_t stream) {
     constexpr int BN = 16 * NT16;
+    constexpr int BMH = 64 * H;
     constexpr int LDB_S = BN + ((NT16 & 1) ? 0 : 16);
-    const size_t smem = 2 * (size_t)(BM * LDA_S + BK * LDB_S) * sizeof(float);  // 64 KiB at NT16 = 7
+    const size_t smem = 2 * (size_t)(BMH * LDA_S + BK * LDB_S) * sizeof(float);  // 64 KiB at NT16 = 7, H = 2
     static bool lds_opt_in = false;
     if (smem > 64 * 1024 && !lds_opt_in) {
-        hipError_t e = hipFuncSetAttribute((const void*)cbm_gemm16_kernel<NT16, VEC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        hipError_t e = hipFuncSetAttribute((const void*)cbm_gemm16_kernel<NT16, H, VEC>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) {
             cbm_set_error_detail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", hipGetErrorString(e));
             return CBM_ERR_HIP;
         }
         lds_opt_in = true;
     }
-    dim3 grid((unsigned)((M + BM - 1) / BM), (unsigned)((N + BN - 1) / BN));
-    hipLaunchKernelGGL((cbm_gemm16_kernel<NT16, VEC>), grid, dim3(256), smem, stream, M, N, K, A, lda, B, ldb, C, ldc);
+    dim3 grid((unsigned)((M + BMH - 1) / BMH), (unsigned)((N + BN - 1) / BN));
+    hipLaunchKernelGGL((cbm_gemm16_kernel<NT16, H, VEC>), grid, dim3(256), smem, stream, M, N, K, A, lda, B, ldb, C, ldc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         cbm_set_error_detail("cbm_gemm16_kernel launch", hipGetErrorString(e));
@@ -340,13 +343,25 @@ cbm_status launch16(int64_t M, int N, int K, const float* A, int64_t lda, const 
     return CBM_OK;
 }
 
+// Share of the busiest compute unit's time that is work, if nblocks equal blocks are dealt evenly over the 256 units.
+inline double cu_balance(int64_t nblocks) {
+    const int64_t per_cu = (nblocks + 255) / 256;
+    return (double)nblocks / (256.0 * (double)per_cu);
+}
+
 template <int NT16>
 cbm_status launch16_nt(int64_t M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, float* C,
                        int64_t ldc, hipStream_t stream) {
     const bool vec = K % 4 == 0 && N % 4 == 0 && lda % 4 == 0 && ldb % 4 == 0 && ((uintptr_t)A & 15) == 0 &&
                      ((uintptr_t)B & 15) == 0 && K >= 4 && N >= 4;
-    return vec ? launch16<NT16, true>(M, N, K, A, lda, B, ldb, C, ldc, stream)
-               : launch16<NT16, false>(M, N, K, A, lda, B, ldb, C, ldc, stream);
+    // blocks of 64 rows where blocks of 128 would leave the compute units unevenly loaded (a few blocks each)
+    static const char* env = std::getenv("CBM_GEMM16_ROWS");
+    const bool half = env ? std::atoi(env) == 64 : cu_balance((M + 63) / 64) > 1.05 * cu_balance((M + 127) / 128);
+    if (half)
+        return vec ? launch16<NT16, 1, true>(M, N, K, A, lda, B, ldb, C, ldc, stream)
+                   : launch16<NT16, 1, false>(M, N, K, A, lda, B, ldb, C, ldc, stream);
+    return vec ? launch16<NT16, 2, true>(M, N, K, A, lda, B, ldb, C, ldc, stream)
+               : launch16<NT16, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream);
 }
 
 template <int NT, bool VEC>

@@ -545,7 +545,9 @@ def test_gcn2_rejects_overlapping_buffers(env, graphs):
                                    (1, 1, 1), (300, 200, 37),
                                    # widths served by the 16-column tiles (N mod 32 in 1..16 above 32), ragged M and K too
                                    (2000, 112, 256), (1029, 100, 61), (515, 48, 128), (640, 40, 36), (300, 80, 500),
-                                   (129, 65, 33), (4100, 97, 5)])
+                                   (129, 65, 33), (4100, 97, 5),
+                                   # as many rows as fill the chip evenly with blocks of 128 rows (fewer rows run in blocks of 64)
+                                   (32768, 112, 40), (32700, 48, 36), (32768, 80, 33)])
 def test_dense_matmul(env, M, N, K):
     torch, cbm = env
     rng = np.random.default_rng(M + N + K)
