@@ -779,7 +779,9 @@ def run(args, wl, store, counters, counters_note):
             A = torch.randn(M, K, device="cuda")
             B = torch.randn(K, N, device="cuda")
             C = torch.empty(M, N, device="cuda")
-            ms = time_steps(torch, lambda: cbm.cbm_dense_matmul(A, B, C), args.steps, args.warmup)
+            # (a long warm-up: the first kernels of a process run before the clocks have settled, and an MFMA-bound
+            # kernel shows it: 10-15 % on the first shape otherwise)
+            ms = time_steps(torch, lambda: cbm.cbm_dense_matmul(A, B, C), args.steps, max(args.warmup, 200))
             res.append(dict(M=M, N=N, K=K, ms=ms, tflops=2.0 * M * N * K / ms / 1e9,
                             frac_of_fp32_mfma_peak=2.0 * M * N * K / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS,
                             GBps=4.0 * (M * K + K * N + M * N) / ms / 1e6))

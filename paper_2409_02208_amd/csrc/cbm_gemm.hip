@@ -13,7 +13,9 @@
 // memory (four 32-bit reads, conflict-free: a half-wave reads 32 consecutive n).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 
 #include "cbm_internal.h"
 
@@ -364,6 +366,240 @@ cbm_status launch16_nt(int64_t M, int N, int K, const float* A, int64_t lda, con
                : launch16<NT16, 2, false>(M, N, K, A, lda, B, ldb, C, ldc, stream);
 }
 
+// Third form, for tall A against a weight panel that fits in LDS (K rows by up to 128 columns, 160 KiB): the panel is loaded
+// once per block and stays; the waves then run free of one another, each streaming its own rows of A straight from memory
+// into MFMA operand registers (no LDS staging of A, no barrier in the loop).  One block of WPB waves per compute unit.
+// Work comes in groups of 32 rows.  Every wave takes the same number of whole groups (a contiguous run of rows, all
+// column tiles of the panel); the groups left over, fewer than there are waves, are cut into chunks of column tiles and
+// spread over the waves, at most one chunk each, so the waves end (nearly) together whatever M is.
+// One 16x16x4 MFMA contracts four k: lane (c = l%16, q = l/16) holds A[row c][k0 + 4q .. 4q+3] of a group of 16 k as one
+// 128-bit load and feeds element e to MFMA e, which therefore contracts k0 + 4q + e over q; the B operand of MFMA e is
+// panel[k0 + 4q + e][16t + c].  The panel's row stride (16 NT16 + 4 floats) puts q and q+1 on disjoint halves of the banks.
+// Loads of A run four groups of 16 k ahead through a ring of registers and are unconditional (addresses clamped into the
+// matrix; what lies beyond K is zeroed when used, rows beyond M are never stored).
+template <int NT16, int WPB>
+__global__ __launch_bounds__(64 * WPB) void cbm_gemm_panel_kernel(int64_t M, int N, int K, int Kp, const float* __restrict__ A, int64_t lda,
+                                                             const float* __restrict__ B, int64_t ldb, float* __restrict__ C,
+                                                             int64_t ldc) {
+    constexpr int BN = 16 * NT16;
+    constexpr int LDB = BN + 4;
+    extern __shared__ float smem[];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: what follows from it stays in scalar registers
+    const int lane = tid & 63;
+    const int c = lane & 15;
+    const int q = lane >> 4;
+    const int nkg = Kp / 16;  // groups of 16 k; Kp is a multiple of 64
+    const int64_t G = (M + 31) / 32;
+    const int64_t nwaves = (int64_t)gridDim.x * WPB;
+    const int64_t gw = (int64_t)blockIdx.x * WPB + wave;
+    const int npanels = (N + BN - 1) / BN;
+
+    // groups [g_begin, g_end) of 32 rows, NTL column tiles from tile0 on, of the panel at column col0
+    // RING groups of 16 k are in flight per wave (nkg is a multiple of RING)
+    auto groups = [&](auto ntl_tag, auto ring_tag, int64_t g_begin, int64_t g_end, int tile0, int col0) {
+        constexpr int NTL = decltype(ntl_tag)::value;
+        constexpr int RING = decltype(ring_tag)::value;
+        float4 ring[RING][2];
+        const float* arow[2];  // this lane's two rows of the group being loaded from
+        auto set_rows = [&](int64_t g) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) arow[h] = A + min(32 * g + 16 * h + c, M - 1) * lda;
+        };
+        auto issue = [&](int j, int kg) {
+            const int k = min(16 * kg + 4 * q, K - 4);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) ring[j][h] = *reinterpret_cast<const float4*>(arow[h] + k);
+        };
+        set_rows(g_begin);
+#pragma unroll
+        for (int j = 0; j < RING; ++j) {
+            issue(j, j);
+            __builtin_amdgcn_sched_barrier(0);  // in this order: the loop waits for the slots oldest first
+        }
+        const float* bcol = smem + 4 * q * LDB + 16 * tile0 + c;
+
+        for (int64_t g = g_begin; g < g_end; ++g) {
+            floatx4 acc[2][NTL];
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int t = 0; t < NTL; ++t)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[h][t][v] = 0.0f;
+
+            for (int kg0 = 0; kg0 < nkg; kg0 += RING) {
+                const bool last = kg0 + RING == nkg;
+                if (last) set_rows(min(g + 1, G - 1));  // the refills of the last pass belong to the next group
+#pragma unroll
+                for (int j = 0; j < RING; ++j) {
+                    const int kg = kg0 + j;
+                    const uint32_t keep = (16 * kg + 4 * q < K) ? 0xffffffffu : 0u;
+                    float a[2][4];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        a[h][0] = __uint_as_float(__float_as_uint(ring[j][h].x) & keep);
+                        a[h][1] = __uint_as_float(__float_as_uint(ring[j][h].y) & keep);
+                        a[h][2] = __uint_as_float(__float_as_uint(ring[j][h].z) & keep);
+                        a[h][3] = __uint_as_float(__float_as_uint(ring[j][h].w) & keep);
+                    }
+                    issue(j, last ? j : kg + RING);  // refill the slot: RING groups of k ahead
+                    const float* bb = bcol + 16 * kg * LDB;
+                    float bf[2][NTL];
+#pragma unroll
+                    for (int t = 0; t < NTL; ++t) bf[0][t] = bb[16 * t];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (e < 3) {
+#pragma unroll
+                            for (int t = 0; t < NTL; ++t) bf[(e + 1) & 1][t] = bb[(e + 1) * LDB + 16 * t];
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int t = 0; t < NTL; ++t) {
+                            acc[0][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0][e], bf[e & 1][t], acc[0][t], 0, 0, 0);
+                            acc[1][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1][e], bf[e & 1][t], acc[1][t], 0, 0, 0);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            }
+
+            // accumulator layout of the 16x16 tile: register v of lane l is row 4*(l/16) + v, column l%16
+            const bool rows_inside = 32 * g + 32 <= M;  // wave-uniform: only the last group of the matrix can be ragged
+#pragma unroll
+            for (int t = 0; t < NTL; ++t) {
+                const int col = col0 + 16 * (tile0 + t) + c;
+                if (col >= N) continue;
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int64_t r = 32 * g + 16 * h + 4 * q + v;
+                        if (rows_inside || r < M) C[r * ldc + col] = acc[h][t][v];
+                    }
+            }
+        }
+    };
+
+    // Two panels: the blocks split into two sets that work side by side, one panel each, on all rows (sets alternate every
+    // 8 blocks, so the two blocks that stream the same rows of A at the same time share an XCD and its L2).  One panel, or
+    // more than two: every block takes the panels one after the other.
+    const bool side_by_side = npanels == 2 && gridDim.x % 16 == 0;
+    const int64_t nw = side_by_side ? nwaves / 2 : nwaves;  // waves that share a panel's rows
+    const int64_t gwp = side_by_side ? ((int64_t)(blockIdx.x / 16) * 8 + blockIdx.x % 8) * WPB + wave : gw;
+    const int p_begin = side_by_side ? (int)(blockIdx.x / 8) % 2 : 0;
+    const int p_end = side_by_side ? p_begin + 1 : npanels;
+    for (int p = p_begin; p < p_end; ++p) {
+        const int col0 = p * BN;
+        const int ntp = min(NT16, (N - col0 + 15) / 16);  // column tiles of this panel that hold columns of C
+        if (p > p_begin) __syncthreads();                  // every wave is done with the previous panel
+        // the panel: eight 128-bit loads per thread in flight at a time, from clamped addresses; what lies outside B is zeroed
+        constexpr int FILL = 8;
+        const int total = Kp * (BN / 4);
+        for (int base = tid; base < total; base += 64 * WPB * FILL) {
+            float4 v[FILL];
+#pragma unroll
+            for (int u = 0; u < FILL; ++u) {
+                const int idx = min(base + 64 * WPB * u, total - 1);
+                const int k = idx / (BN / 4), col = col0 + (idx % (BN / 4)) * 4;
+                v[u] = *reinterpret_cast<const float4*>(B + (int64_t)min(k, K - 1) * ldb + min(col, N - 4));  // N % 4 == 0
+                if (k >= K || col >= N) v[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            }
+#pragma unroll
+            for (int u = 0; u < FILL; ++u) {
+                const int idx = base + 64 * WPB * u;
+                if (idx < total) *reinterpret_cast<float4*>(smem + (idx / (BN / 4)) * LDB + (idx % (BN / 4)) * 4) = v[u];
+            }
+        }
+        __syncthreads();
+
+        const int64_t each = G / nw;  // whole groups per wave
+        const int64_t left0 = each * nw;
+        // The groups left over (fewer than there are waves) are cut into chunks of 1, 2, 4 or all column tiles: the
+        // smallest chunk that still gives no wave more than one.  They go first: a narrow chunk waits on memory more
+        // than it computes (so it keeps more of K in flight), and the wave it shares its SIMD with has whole groups to
+        // fill the matrix pipe meanwhile.  The chunks are spread evenly over the blocks (every stride-th wave takes one).
+        int chunk = NT16;
+        if ((G - left0) * ntp <= nw) chunk = 1;
+        else if (NT16 > 2 && (G - left0) * ((ntp + 1) / 2) <= nw) chunk = 2;
+        else if (NT16 > 4 && (G - left0) * ((ntp + 3) / 4) <= nw) chunk = 4;
+        const int nchunks = (ntp + chunk - 1) / chunk;
+        const int64_t ntasks = (G - left0) * nchunks;
+        const int64_t stride = ntasks > 0 ? nw / ntasks : 1;
+        if (gwp % stride == 0 && gwp / stride < ntasks) {
+            const int64_t task = gwp / stride;
+            const int64_t g = left0 + task / nchunks;
+            const int t = min((int)(task % nchunks) * chunk, NT16 - chunk);  // (a last chunk that would overhang moves left)
+            if (chunk == 1) {
+                if (WPB <= 8 && nkg % 16 == 0)  // (with more waves per SIMD the registers do not stretch to sixteen)
+                    groups(std::integral_constant<int, 1>{}, std::integral_constant<int, WPB <= 8 ? 16 : 8>{}, g, g + 1, t, col0);
+                else if (nkg % 8 == 0)
+                    groups(std::integral_constant<int, 1>{}, std::integral_constant<int, 8>{}, g, g + 1, t, col0);
+                else
+                    groups(std::integral_constant<int, 1>{}, std::integral_constant<int, 4>{}, g, g + 1, t, col0);
+            } else if (NT16 > 2 && chunk == 2) {
+                if (nkg % 8 == 0)
+                    groups(std::integral_constant<int, (NT16 > 2 ? 2 : 1)>{}, std::integral_constant<int, 8>{}, g, g + 1, t, col0);
+                else
+                    groups(std::integral_constant<int, (NT16 > 2 ? 2 : 1)>{}, std::integral_constant<int, 4>{}, g, g + 1, t, col0);
+            } else if (NT16 > 4 && chunk == 4) {
+                groups(std::integral_constant<int, (NT16 > 4 ? 4 : 1)>{}, std::integral_constant<int, 4>{}, g, g + 1, t, col0);
+            } else {
+                groups(std::integral_constant<int, NT16>{}, std::integral_constant<int, 4>{}, g, g + 1, 0, col0);
+            }
+        }
+        if (each > 0)
+            groups(std::integral_constant<int, NT16>{}, std::integral_constant<int, 4>{}, gwp * each, (gwp + 1) * each, 0, col0);
+    }
+}
+
+template <int NT16>
+cbm_status launch_panel(int64_t M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
+                        size_t smem, hipStream_t stream);
+
+// LDS bytes of the resident panel, or 0 if this product cannot take the panel kernel.
+inline size_t panel_lds_bytes(int64_t M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, int* nt16) {
+    const bool vec = K % 4 == 0 && N % 4 == 0 && lda % 4 == 0 && ldb % 4 == 0 && ((uintptr_t)A & 15) == 0 &&
+                     ((uintptr_t)B & 15) == 0 && K >= 4 && N >= 4;
+    if (!vec || N < 16) return 0;
+    const int tiles = (N + 15) / 16, npanels = (tiles + 7) / 8;
+    *nt16 = (tiles + npanels - 1) / npanels;  // panels of equal width, at most 128 columns
+    const int64_t Kp = ((int64_t)K + 63) / 64 * 64;
+    const size_t bytes = (size_t)Kp * (16 * *nt16 + 4) * sizeof(float);
+    return bytes <= 160 * 1024 ? bytes : 0;
+}
+
+template <int NT16, int WPB>
+cbm_status launch_panel_w(int64_t M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
+                        size_t smem, hipStream_t stream) {
+    static size_t lds_opt_in = 0;  // buffers above 64 KiB need the per-kernel opt-in; raised when a larger one comes
+    if (smem > 64 * 1024 && smem > lds_opt_in) {
+        hipError_t e = hipFuncSetAttribute((const void*)cbm_gemm_panel_kernel<NT16, WPB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) {
+            cbm_set_error_detail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", hipGetErrorString(e));
+            return CBM_ERR_HIP;
+        }
+        lds_opt_in = smem;
+    }
+    const int Kp = (K + 63) / 64 * 64;
+    hipLaunchKernelGGL((cbm_gemm_panel_kernel<NT16, WPB>), dim3(256), dim3(64 * WPB), smem, stream, M, N, K, Kp, A, lda, B, ldb, C, ldc);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        cbm_set_error_detail("cbm_gemm_panel_kernel launch", hipGetErrorString(e));
+        return CBM_ERR_HIP;
+    }
+    return CBM_OK;
+}
+
+template <int NT16>
+cbm_status launch_panel(int64_t M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
+                        size_t smem, hipStream_t stream) {
+    // (twelve waves per block were measured slower: fewer whole groups per wave, more of the work in narrow chunks)
+    return launch_panel_w<NT16, 8>(M, N, K, A, lda, B, ldb, C, ldc, smem, stream);
+}
+
 template <int NT, bool VEC>
 cbm_status launch(int64_t M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
                   hipStream_t stream) {
@@ -408,6 +644,24 @@ cbm_status cbm_launch_gemm(int64_t M, int32_t N, int32_t K, const float* A, int6
         if (hipMemset2DAsync(C, (size_t)ldc * sizeof(float), 0, (size_t)N * sizeof(float), (size_t)M, stream) != hipSuccess)
             return CBM_ERR_HIP;
         return CBM_OK;
+    }
+    {   // tall A, a weight panel that fits in LDS: the panel-resident kernel
+        static const char* env = std::getenv("CBM_GEMM_PANEL_MIN_ROWS");
+        const int64_t min_rows = env ? std::atoll(env) : 8192;
+        int nt16 = 0;
+        const size_t smem = M >= min_rows ? panel_lds_bytes(M, N, K, A, lda, B, ldb, &nt16) : 0;
+        if (smem) {
+            switch (nt16) {
+                case 1: return launch_panel<1>(M, N, K, A, lda, B, ldb, C, ldc, smem, stream);
+                case 2: return launch_panel<2>(M, N, K, A, lda, B, ldb, C, ldc, smem, stream);
+                case 3: return launch_panel<3>(M, N, K, A, lda, B, ldb, C, ldc, smem, stream);
+                case 4: return launch_panel<4>(M, N, K, A, lda, B, ldb, C, ldc, smem, stream);
+                case 5: return launch_panel<5>(M, N, K, A, lda, B, ldb, C, ldc, smem, stream);
+                case 6: return launch_panel<6>(M, N, K, A, lda, B, ldb, C, ldc, smem, stream);
+                case 7: return launch_panel<7>(M, N, K, A, lda, B, ldb, C, ldc, smem, stream);
+                default: return launch_panel<8>(M, N, K, A, lda, B, ldb, C, ldc, smem, stream);
+            }
+        }
     }
     // widths that would leave more than half of the last 32-column tile empty go to the 16-column tiles
     if (N > 32 && N <= 48) return launch16_nt<3>(M, N, K, A, lda, B, ldb, C, ldc, stream);

@@ -547,7 +547,15 @@ def test_gcn2_rejects_overlapping_buffers(env, graphs):
                                    (2000, 112, 256), (1029, 100, 61), (515, 48, 128), (640, 40, 36), (300, 80, 500),
                                    (129, 65, 33), (4100, 97, 5),
                                    # as many rows as fill the chip evenly with blocks of 128 rows (fewer rows run in blocks of 64)
-                                   (32768, 112, 40), (32700, 48, 36), (32768, 80, 33)])
+                                   (32768, 112, 40), (32700, 48, 36), (32768, 80, 33),
+                                   # tall enough for the panel-resident kernel: one and two panels, ragged rows, K not a
+                                   # multiple of 64, widths that are not a multiple of 16, leftover groups cut into tiles
+                                   (70001, 112, 256), (65536, 256, 256), (9000, 64, 500), (20011, 200, 100), (8192, 16, 4),
+                                   (33333, 132, 68), (12345, 20, 260), (66000, 128, 64),
+                                   # leftover groups cut into chunks of two and of four tiles (with a last chunk that
+                                   # overlaps its neighbour at seven tiles), three panels one after the other
+                                   (78336, 128, 64), (78341, 128, 128), (91136, 128, 64), (78341, 112, 128), (91136, 112, 64),
+                                   (9000, 300, 64)])
 def test_dense_matmul(env, M, N, K):
     torch, cbm = env
     rng = np.random.default_rng(M + N + K)
