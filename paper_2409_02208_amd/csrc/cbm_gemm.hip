@@ -1,7 +1,10 @@
-// Dense fp32 matmul C = A.B on the gfx950 matrix cores (v_mfma_f32_32x32x2_f32),
-// for the X.W products of the two-layer GCN (Eq. (1)).  A is tall (one row per
-// graph node), B is a small weight matrix.
+// Dense fp32 matmul C = A.B on the gfx950 matrix cores, for the X.W products of
+// the two-layer GCN (Eq. (1)).  A is tall (one row per graph node), B is a small
+// weight matrix.  Three kernels: tall products whose weight panel fits in LDS take
+// the panel-resident kernel further down (cbm_gemm_panel_kernel); the rest are
+// staged through LDS slabs, on 32x32x2 tiles (first kernel) or 16x16x4 tiles.
 //
+// First kernel (v_mfma_f32_32x32x2_f32):
 // Block = 4 waves = 128 rows of C by BN = 32*NT columns; each wave owns 32 rows
 // and NT 32x32 accumulator tiles.  K is walked in slabs of 32 through two LDS
 // buffers; the next slab is fetched into registers while the current one is
