@@ -716,6 +716,8 @@ def alpha_sweep(args, torch, cbm, wl):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--gemm-shapes", default="", help="with --probe-gemm: comma-separated MxNxK instead of the GCN shapes")
+    ap.add_argument("--gemm-vendor", action="store_true", help="with --probe-gemm: time torch.matmul on the same operands too")
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="rmat", choices=list(DEFAULTS))
@@ -775,7 +777,10 @@ def run(args, wl, store, counters, counters_note):
         return
     if args.probe_gemm:
         res = []
-        for M, N, K in ((132534, 256, 256), (132534, 112, 256), (19717, 64, 500), (19717, 3, 64)):
+        shapes = ((132534, 256, 256), (132534, 112, 256), (19717, 64, 500), (19717, 3, 64))
+        if args.gemm_shapes:
+            shapes = tuple(tuple(int(v) for v in sh.split("x")) for sh in args.gemm_shapes.split(","))
+        for M, N, K in shapes:
             A = torch.randn(M, K, device="cuda")
             B = torch.randn(K, N, device="cuda")
             C = torch.empty(M, N, device="cuda")
@@ -785,7 +790,12 @@ def run(args, wl, store, counters, counters_note):
             res.append(dict(M=M, N=N, K=K, ms=ms, tflops=2.0 * M * N * K / ms / 1e9,
                             frac_of_fp32_mfma_peak=2.0 * M * N * K / ms / 1e9 / FP32_MFMA_PEAK_TFLOPS,
                             GBps=4.0 * (M * K + K * N + M * N) / ms / 1e6))
-            log(f"matmul {M}x{K} . {K}x{N}: {ms:.4f} ms, {res[-1]['tflops']:.1f} TFLOP/s")
+            vendor = ""
+            if args.gemm_vendor:   # the vendor's library through torch.matmul on the same operands, as outside context
+                ms_v = time_steps(torch, lambda: torch.matmul(A, B, out=C), args.steps, 20)
+                res[-1].update(vendor_ms=ms_v, vendor_tflops=2.0 * M * N * K / ms_v / 1e9)
+                vendor = f"; torch.matmul {ms_v:.4f} ms, {res[-1]['vendor_tflops']:.1f} TFLOP/s"
+            log(f"matmul {M}x{K} . {K}x{N}: {ms:.4f} ms, {res[-1]['tflops']:.1f} TFLOP/s{vendor}")
         print(json.dumps({"probe": "gemm", "dtype": "f32", "peak_tflops": FP32_MFMA_PEAK_TFLOPS, "shapes": res}))
         return
     if args.alpha_sweep:
