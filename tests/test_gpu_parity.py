@@ -575,6 +575,31 @@ def test_dense_matmul(env, M, N, K):
     assert np.array_equal(Cd.cpu().numpy().astype(np.float64), Ai.astype(np.float64) @ Bi.astype(np.float64))
 
 
+@pytest.mark.parametrize("M,N,K,pad_a,pad_b,pad_c,off", [(40000, 112, 256, 8, 16, 4, 4),    # panel kernel, strided, aligned
+                                                          (40000, 256, 128, 4, 0, 12, 8),    # two panels side by side
+                                                          (40000, 112, 256, 8, 16, 4, 1),    # slices off the 16-byte grid
+                                                          (40000, 96, 64, 3, 5, 1, 0)])      # odd strides: staged kernels
+def test_dense_matmul_strided_operands(env, M, N, K, pad_a, pad_b, pad_c, off):
+    """A, B and C as column slices of wider buffers (leading dimensions larger than the widths), output rows poisoned:
+    nothing outside C's columns may be written."""
+    torch, cbm = env
+    rng = np.random.default_rng(M + N + K + off)
+    Aw = rng.standard_normal((M, K + pad_a + off)).astype(np.float32)
+    Bw = rng.standard_normal((K, N + pad_b + off)).astype(np.float32)
+    Ad, Bd = torch.from_numpy(Aw).cuda(), torch.from_numpy(Bw).cuda()
+    Cw = torch.full((M, N + pad_c + off), float("nan"), device="cuda")
+    A, B, C = Ad[:, off:off + K], Bd[:, off:off + N], Cw[:, off:off + N]
+    cbm.cbm_dense_matmul(A, B, C)
+    torch.cuda.synchronize()
+    a64, b64 = Aw[:, off:off + K].astype(np.float64), Bw[:, off:off + N].astype(np.float64)
+    bound = 2.0 * K * 2.0 ** -24 * (np.abs(a64) @ np.abs(b64))
+    got = Cw.cpu().numpy()
+    assert np.all(np.abs(got[:, off:off + N] - a64 @ b64) <= bound + 1e-30)
+    outside = np.ones(got.shape[1], dtype=bool)
+    outside[off:off + N] = False
+    assert np.isnan(got[:, outside]).all()
+
+
 @pytest.mark.parametrize("name,f_in,hidden,f_out", [("citation", 500, 64, 3), ("protein", 256, 256, 112),
                                                     ("tiny", 16, 8, 4)])
 def test_gcn2_forward(env, graphs, name, f_in, hidden, f_out):
