@@ -371,7 +371,8 @@ cbm_status launch16_nt(int64_t M, int N, int K, const float* A, int64_t lda, con
 
 // Third form, for tall A against a weight panel that fits in LDS (K rows by up to 128 columns, 160 KiB): the panel is loaded
 // once per block and stays; the waves then run free of one another, each streaming its own rows of A straight from memory
-// into MFMA operand registers (no LDS staging of A, no barrier in the loop).  One block of WPB waves per compute unit.
+// into MFMA operand registers (no LDS staging of A, no barrier in the loop).  One block of 8 waves per compute unit
+// (twelve were measured slower: fewer whole groups per wave, more of the work in narrow chunks).
 // Work comes in groups of 32 rows.  Every wave takes the same number of whole groups (a contiguous run of rows, all
 // column tiles of the panel); the groups left over, fewer than there are waves, are cut into chunks of column tiles and
 // spread over the waves, at most one chunk each, so the waves end (nearly) together whatever M is.
@@ -380,7 +381,9 @@ cbm_status launch16_nt(int64_t M, int N, int K, const float* A, int64_t lda, con
 // panel[k0 + 4q + e][16t + c].  The panel's row stride (16 NT16 + 4 floats) puts q and q+1 on disjoint halves of the banks.
 // Loads of A run four groups of 16 k ahead through a ring of registers and are unconditional (addresses clamped into the
 // matrix; what lies beyond K is zeroed when used, rows beyond M are never stored).
-template <int NT16, int WPB>
+constexpr int WPB = 8;  // waves per block of the panel kernel
+
+template <int NT16>
 __global__ __launch_bounds__(64 * WPB) void cbm_gemm_panel_kernel(int64_t M, int N, int K, int Kp, const float* __restrict__ A, int64_t lda,
                                                              const float* __restrict__ B, int64_t ldb, float* __restrict__ C,
                                                              int64_t ldc) {
@@ -536,8 +539,8 @@ __global__ __launch_bounds__(64 * WPB) void cbm_gemm_panel_kernel(int64_t M, int
             const int64_t g = left0 + task / nchunks;
             const int t = min((int)(task % nchunks) * chunk, NT16 - chunk);  // (a last chunk that would overhang moves left)
             if (chunk == 1) {
-                if (WPB <= 8 && nkg % 16 == 0)  // (with more waves per SIMD the registers do not stretch to sixteen)
-                    groups(std::integral_constant<int, 1>{}, std::integral_constant<int, WPB <= 8 ? 16 : 8>{}, g, g + 1, t, col0);
+                if (nkg % 16 == 0)
+                    groups(std::integral_constant<int, 1>{}, std::integral_constant<int, 16>{}, g, g + 1, t, col0);
                 else if (nkg % 8 == 0)
                     groups(std::integral_constant<int, 1>{}, std::integral_constant<int, 8>{}, g, g + 1, t, col0);
                 else
@@ -558,10 +561,6 @@ __global__ __launch_bounds__(64 * WPB) void cbm_gemm_panel_kernel(int64_t M, int
     }
 }
 
-template <int NT16>
-cbm_status launch_panel(int64_t M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
-                        size_t smem, hipStream_t stream);
-
 // LDS bytes of the resident panel, or 0 if this product cannot take the panel kernel.
 inline size_t panel_lds_bytes(int64_t M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, int* nt16) {
     const bool vec = K % 4 == 0 && N % 4 == 0 && lda % 4 == 0 && ldb % 4 == 0 && ((uintptr_t)A & 15) == 0 &&
@@ -574,12 +573,12 @@ inline size_t panel_lds_bytes(int64_t M, int N, int K, const float* A, int64_t l
     return bytes <= 160 * 1024 ? bytes : 0;
 }
 
-template <int NT16, int WPB>
-cbm_status launch_panel_w(int64_t M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
+template <int NT16>
+cbm_status launch_panel(int64_t M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
                         size_t smem, hipStream_t stream) {
     static size_t lds_opt_in = 0;  // buffers above 64 KiB need the per-kernel opt-in; raised when a larger one comes
     if (smem > 64 * 1024 && smem > lds_opt_in) {
-        hipError_t e = hipFuncSetAttribute((const void*)cbm_gemm_panel_kernel<NT16, WPB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        hipError_t e = hipFuncSetAttribute((const void*)cbm_gemm_panel_kernel<NT16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) {
             cbm_set_error_detail("hipFuncSetAttribute(MaxDynamicSharedMemorySize)", hipGetErrorString(e));
             return CBM_ERR_HIP;
@@ -587,20 +586,13 @@ cbm_status launch_panel_w(int64_t M, int N, int K, const float* A, int64_t lda, 
         lds_opt_in = smem;
     }
     const int Kp = (K + 63) / 64 * 64;
-    hipLaunchKernelGGL((cbm_gemm_panel_kernel<NT16, WPB>), dim3(256), dim3(64 * WPB), smem, stream, M, N, K, Kp, A, lda, B, ldb, C, ldc);
+    hipLaunchKernelGGL((cbm_gemm_panel_kernel<NT16>), dim3(256), dim3(64 * WPB), smem, stream, M, N, K, Kp, A, lda, B, ldb, C, ldc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         cbm_set_error_detail("cbm_gemm_panel_kernel launch", hipGetErrorString(e));
         return CBM_ERR_HIP;
     }
     return CBM_OK;
-}
-
-template <int NT16>
-cbm_status launch_panel(int64_t M, int N, int K, const float* A, int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc,
-                        size_t smem, hipStream_t stream) {
-    // (twelve waves per block were measured slower: fewer whole groups per wave, more of the work in narrow chunks)
-    return launch_panel_w<NT16, 8>(M, N, K, A, lda, B, ldb, C, ldc, smem, stream);
 }
 
 template <int NT, bool VEC>
