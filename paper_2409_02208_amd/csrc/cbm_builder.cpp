@@ -29,7 +29,7 @@ constexpr int32_t kDefaultHubCap = 512;
 constexpr int32_t kDefaultMaxCand = 8;
 constexpr int64_t kLocalityMinEntries = 32;  // mean entries per work item from which a round is scheduled by locality
 constexpr double kLocalityEntries = 230.0;   // such a round's bandwidth grows by 1/230 of the base per entry in a work item
-constexpr int64_t kBundleMinEntries = 128;  // mean entries per work item from which a round's paths are bundled
+constexpr int64_t kBundleMinEntries = 96;   // mean entries per work item from which a round's paths are bundled
 constexpr int64_t kDeviceSearchMinRows = 65536;  // from here on a handle bound for a GPU searches its candidates there
 constexpr int64_t kSampleMinRows = 65536;  // automatic mode samples the compressibility of matrices this large first
 constexpr int32_t kSplitLenDefault = 512;  // most delta entries in one segment of a split row
@@ -209,6 +209,7 @@ struct Builder {
     int64_t split_min = 0, split_len = 0;
     bool bundle = false;  // rounds of long work items are emitted as bundles: a path's deltas in one sweep over the columns
     int64_t bundle_min = kBundleMinEntries;  // mean entries per work item from which a round is bundled (CBM_BUNDLE_MIN)
+    int64_t locality_min = kLocalityMinEntries;  // ... from which a round is scheduled by locality (CBM_LOCALITY_MIN)
     std::vector<uint8_t> cap_rows_in_round;  // rounds whose paths plan() holds to CBM_BUNDLE_ROWS rows
     void choose_bundled_rounds(int64_t path_max, int32_t* nrounds);
     bool is_split(int64_t x) const { return dlen(x) > split_min; }
@@ -830,7 +831,7 @@ double Builder::plan(int64_t path_max, int32_t* nrounds_out) {
         double round_us = 0.0, bytes_us = 0.0;
         if (entries[r] + rows[r] > 0) {
             // a round of long work items is scheduled by graph locality (see emit): more of its gathers hit in L2
-            const bool local = locality && heads[r] >= 64 * CBM_XCD && entries[r] + written[r] >= kLocalityMinEntries * heads[r];
+            const bool local = locality && heads[r] >= 64 * CBM_XCD && entries[r] + written[r] >= locality_min * heads[r];
             // measured on the protein recipe: 1.25x the base rate at 68 entries per work item, 1.6x at 130, 2.4x at 320
             const double per_item = heads[r] > 0 ? (double)(entries[r] + written[r]) / (double)heads[r] : 0.0;
             // ... and less when there are too few long items to fill the chip (2,500 of them: 0.6 of the rate of 12,000)
@@ -1114,7 +1115,7 @@ cbm_status Builder::emit(int32_t nrounds) {
         for (auto& t : lt) round_entries += (t.len_flags & CBM_TASK_LEN_MASK);
         // worth it for rounds of long work items (protein: 8 % faster); rounds of short ones lose more to the
         // ragged tail of each XCD's block than they gain (and a graph without a tree has no such order at all)
-        if (by_locality && (int64_t)lt.size() >= 64 * CBM_XCD && round_entries >= kLocalityMinEntries * (int64_t)lt.size()) {
+        if (by_locality && (int64_t)lt.size() >= 64 * CBM_XCD && round_entries >= locality_min * (int64_t)lt.size()) {
             // neighbours in the graph next to each other, one contiguous share of the entries per XCD: what the
             // work items running on an XCD at one time gather overlaps, and stays in that XCD's L2
             std::stable_sort(lt.begin(), lt.end(), [&](const CbmTask& a, const CbmTask& b2) { return loc[a.row] < loc[b2.row]; });
@@ -1128,6 +1129,15 @@ cbm_status Builder::emit(int32_t nrounds) {
                 while (i < lt.size() && (j == CBM_XCD - 1 || seen < want)) seen += (lt[i++].len_flags & CBM_TASK_LEN_MASK);
                 R.xcd_count[j] = R.task_begin + (int64_t)i - R.xcd_begin[j];
             }
+            // Inside a share the longest work items go first (ties keep the locality order): which XCD gathers what is
+            // what the locality is about, and a long item that starts last is the tail of the whole launch (protein
+            // product: 1.05 -> 0.83 ms; windows of 64 or 512 items, or only the longer half first, gain little or half).
+            static const bool share_longest_first = !std::getenv("CBM_NO_SHARE_SORT");
+            if (share_longest_first)
+                for (int j = 0; j < CBM_XCD; ++j) {
+                    auto b = lt.begin() + (R.xcd_begin[j] - R.task_begin);
+                    std::stable_sort(b, b + R.xcd_count[j], longest_first);
+                }
         } else {
             std::stable_sort(lt.begin(), lt.end(), longest_first);
         }
@@ -1312,6 +1322,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     B.locality = m == n && !std::getenv("CBM_NO_LOCALITY");
     B.bundle = tree && n <= (int64_t)CBM_BUNDLE_INDEX_MASK && !std::getenv("CBM_NO_BUNDLE");
     B.bundle_min = env_clamped("CBM_BUNDLE_MIN", kBundleMinEntries, 1, 1 << 20);
+    B.locality_min = env_clamped("CBM_LOCALITY_MIN", kLocalityMinEntries, 1, 1 << 20);
     const bool exact_tree = (o.flags & CBM_FLAG_EXACT_TREE) != 0;
     if (o.flags & CBM_FLAG_DEVICE_BUILD) {  // asked for: an error if it cannot be had
         if ((o.flags & (CBM_FLAG_HOST_ONLY | CBM_FLAG_HOST_SEARCH)) || B.max_cand < 1 || B.max_cand > 16) return CBM_ERR_INVALID_ARG;
