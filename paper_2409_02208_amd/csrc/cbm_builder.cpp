@@ -30,6 +30,7 @@ constexpr int32_t kDefaultMaxCand = 8;
 constexpr int64_t kLocalityMinEntries = 32;  // mean entries per work item from which a round is scheduled by locality
 constexpr double kLocalityEntries = 230.0;   // such a round's bandwidth grows by 1/230 of the base per entry in a work item
 constexpr int64_t kBundleMinEntries = 96;   // mean entries per work item from which a round's paths are bundled
+constexpr int64_t kBundleMinItems = 256;    // ... and the work items it must have: a round of a few long paths gains nothing from sweeps in step
 constexpr int64_t kDeviceSearchMinRows = 65536;  // from here on a handle bound for a GPU searches its candidates there
 constexpr int64_t kSampleMinRows = 65536;  // automatic mode samples the compressibility of matrices this large first
 constexpr int32_t kSplitLenDefault = 512;  // most delta entries in one segment of a split row
@@ -209,6 +210,7 @@ struct Builder {
     int64_t split_min = 0, split_len = 0;
     bool bundle = false;  // rounds of long work items are emitted as bundles: a path's deltas in one sweep over the columns
     int64_t bundle_min = kBundleMinEntries;  // mean entries per work item from which a round is bundled (CBM_BUNDLE_MIN)
+    int64_t bundle_min_items = kBundleMinItems;  // work items a round needs before its paths are cut for bundling (CBM_BUNDLE_MIN_ITEMS)
     int64_t locality_min = kLocalityMinEntries;  // ... from which a round is scheduled by locality (CBM_LOCALITY_MIN)
     std::vector<uint8_t> cap_rows_in_round;  // rounds whose paths plan() holds to CBM_BUNDLE_ROWS rows
     void choose_bundled_rounds(int64_t path_max, int32_t* nrounds);
@@ -871,7 +873,7 @@ void Builder::choose_bundled_rounds(int64_t path_max, int32_t* nrounds) {
     cap_rows_in_round.assign(*nrounds + 2, 0);
     bool any = false;
     for (int r = 1; r <= *nrounds; ++r)
-        if (multi[r] && ent[r] >= bundle_min * items[r]) cap_rows_in_round[r] = 1, any = true;
+        if (multi[r] && items[r] >= bundle_min_items && ent[r] >= bundle_min * items[r]) cap_rows_in_round[r] = 1, any = true;
     if (!any) return;
     const int32_t before = *nrounds;
     plan(path_max, nrounds);  // (the limits stay in force for every later plan() of this build)
@@ -1322,6 +1324,7 @@ cbm_status cbm_build_host(int64_t m, int64_t n, const int64_t* in_rowptr, const 
     B.locality = m == n && !std::getenv("CBM_NO_LOCALITY");
     B.bundle = tree && n <= (int64_t)CBM_BUNDLE_INDEX_MASK && !std::getenv("CBM_NO_BUNDLE");
     B.bundle_min = env_clamped("CBM_BUNDLE_MIN", kBundleMinEntries, 1, 1 << 20);
+    B.bundle_min_items = env_clamped("CBM_BUNDLE_MIN_ITEMS", kBundleMinItems, 1, 1 << 30);
     B.locality_min = env_clamped("CBM_LOCALITY_MIN", kLocalityMinEntries, 1, 1 << 20);
     const bool exact_tree = (o.flags & CBM_FLAG_EXACT_TREE) != 0;
     if (o.flags & CBM_FLAG_DEVICE_BUILD) {  // asked for: an error if it cannot be had

@@ -461,9 +461,11 @@ def test_bundled_rounds_give_the_same_products(env, graphs, name, monkeypatch):
     torch, cbm = env
     g = graphs[name]
     monkeypatch.setenv("CBM_BUNDLE_MIN", "1")
+    monkeypatch.setenv("CBM_BUNDLE_MIN_ITEMS", "1")
     h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=1, max_depth=16)
     hp = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, alpha=0, max_depth=16)   # (an unbounded tree would give the row limit up)
     monkeypatch.delenv("CBM_BUNDLE_MIN")
+    monkeypatch.delenv("CBM_BUNDLE_MIN_ITEMS")
     s = cbm.cbm_stats(h)
     assert s["bundled_rounds"] >= 1 and cbm.cbm_stats(hp)["bundled_rounds"] >= 1 and s["num_internal"] > 0
     Xi = wl.integer_features(g.n, 16, g.meta["seed"])

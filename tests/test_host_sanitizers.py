@@ -24,7 +24,7 @@ def test_builder_is_clean_under_asan_ubsan(tmp_path):
     r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
     assert r.returncode == 0 and "asan run ok" in r.stdout, (r.stdout[-500:], r.stderr[-3000:])
     # once more with every multi-row round emitted as bundles (one sweep per path, rows tagged in the entries)
-    r = subprocess.run([exe], capture_output=True, text=True, env=dict(env, CBM_BUNDLE_MIN="1"), timeout=300)
+    r = subprocess.run([exe], capture_output=True, text=True, env=dict(env, CBM_BUNDLE_MIN="1", CBM_BUNDLE_MIN_ITEMS="1"), timeout=300)
     assert r.returncode == 0 and "asan run ok" in r.stdout, (r.stdout[-500:], r.stderr[-3000:])
 
 
