@@ -27,9 +27,11 @@ namespace {
 constexpr int32_t kDefaultMaxDepth = 16;
 constexpr int32_t kDefaultHubCap = 512;
 constexpr int32_t kDefaultMaxCand = 8;
-constexpr int64_t kLocalityMinEntries = 32;  // mean entries per work item from which a round is scheduled by locality
+constexpr int64_t kLocalityMinEntries = 24;  // mean entries per work item from which a round is scheduled by locality
 constexpr double kLocalityEntries = 230.0;   // such a round's bandwidth grows by 1/230 of the base per entry in a work item
 constexpr int64_t kBundleMinEntries = 96;   // mean entries per work item from which a round's paths are bundled
+constexpr int64_t kShareSortItems = 8192;   // work items in an XCD's share of a round up to which they run strictly longest first
+constexpr long kShareBucket = 32;           // ... beyond that: by length in buckets of this many entries, locality order inside
 constexpr int64_t kBundleMinItems = 256;    // ... and the work items it must have: a round of a few long paths gains nothing from sweeps in step
 constexpr int64_t kDeviceSearchMinRows = 65536;  // from here on a handle bound for a GPU searches its candidates there
 constexpr int64_t kSampleMinRows = 65536;  // automatic mode samples the compressibility of matrices this large first
@@ -1131,15 +1133,23 @@ cbm_status Builder::emit(int32_t nrounds) {
                 while (i < lt.size() && (j == CBM_XCD - 1 || seen < want)) seen += (lt[i++].len_flags & CBM_TASK_LEN_MASK);
                 R.xcd_count[j] = R.task_begin + (int64_t)i - R.xcd_begin[j];
             }
-            // Inside a share the longest work items go first (ties keep the locality order): which XCD gathers what is
-            // what the locality is about, and a long item that starts last is the tail of the whole launch (protein
-            // product: 1.05 -> 0.83 ms; windows of 64 or 512 items, or only the longer half first, gain little or half).
-            static const bool share_longest_first = !std::getenv("CBM_NO_SHARE_SORT");
-            if (share_longest_first)
-                for (int j = 0; j < CBM_XCD; ++j) {
-                    auto b = lt.begin() + (R.xcd_begin[j] - R.task_begin);
+            // Inside a share the longest work items go first: which XCD gathers what is what the locality is about, and
+            // a long item that starts last is the tail of the whole launch (protein product: 1.05 -> 0.80 ms; only the
+            // longer half first gains half of that).  A share of very many short items has no tail to speak of and lives
+            // on neighbours running side by side instead (collaboration graph with every row stored in full: 0.44 ms in
+            // locality order, 0.54 ms longest-first): there the order is by length only in buckets of 32 entries,
+            // locality order inside a bucket.  CBM_SHARE_SORT: 0 = locality order, 1 = longest first, n = buckets of n.
+            static const long share_mode = env_clamped("CBM_SHARE_SORT", -1, -1, 1 << 20);
+            for (int j = 0; j < CBM_XCD; ++j) {
+                auto b = lt.begin() + (R.xcd_begin[j] - R.task_begin);
+                const long mode = share_mode >= 0 ? share_mode : (R.xcd_count[j] <= kShareSortItems ? 1 : kShareBucket);
+                if (mode == 1)
                     std::stable_sort(b, b + R.xcd_count[j], longest_first);
-                }
+                else if (mode > 1)
+                    std::stable_sort(b, b + R.xcd_count[j], [&](const CbmTask& x, const CbmTask& y) {
+                        return (x.len_flags & CBM_TASK_LEN_MASK) / mode > (y.len_flags & CBM_TASK_LEN_MASK) / mode;
+                    });
+            }
         } else {
             std::stable_sort(lt.begin(), lt.end(), longest_first);
         }
