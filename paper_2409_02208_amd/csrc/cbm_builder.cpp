@@ -1066,6 +1066,22 @@ cbm_status Builder::emit(int32_t nrounds) {
     // (workgroup id mod 8), so the popular rows of X in that range stay in that XCD's L2.  Very long rows are cut
     // finer still: each XCD's range is walked in `phases` sub-ranges, one after the other, so that at any time an
     // XCD gathers from 1/(8 phases) of X.
+    // The boundaries give every range an equal share of the split rows' entries (equal widths would overload one XCD
+    // on a matrix whose popular columns sit together in the index range); cut[f] = first column of fine piece f.
+    std::vector<uint32_t> cut((size_t)CBM_XCD * phases + 1, 0);
+    {
+        const int P = CBM_XCD * phases;
+        std::vector<int64_t> upto((size_t)n + 1, 0);  // entries of split rows in columns < c
+        for (const Piece& sp : splits)
+            for (int64_t i = 0; i < dlen(sp.x); ++i) ++upto[(h->stream[sp.base + i] & CBM_ENTRY_INDEX_MASK) + 1];
+        for (int64_t c2 = 0; c2 < n; ++c2) upto[c2 + 1] += upto[c2];
+        const int64_t total = upto[n];
+        for (int f = 1; f < P; ++f)
+            cut[f] = total > 0 ? (uint32_t)(std::lower_bound(upto.begin(), upto.end(), (total * f + P - 1) / P) - upto.begin())
+                               : (uint32_t)((int64_t)f * n / P);
+        cut[P] = (uint32_t)n;
+        for (int f = 1; f <= P; ++f) cut[f] = std::min<uint32_t>((uint32_t)n, std::max(cut[f], cut[f - 1]));
+    }
     for (const Piece& sp : splits) {
         const int32_t x = sp.x;
         const int32_t y = h->parent[x];
@@ -1079,7 +1095,7 @@ cbm_status Builder::emit(int32_t nrounds) {
         const int npieces = CBM_XCD * fine;
         int64_t pos = 0;
         for (int f = 0; f < npieces; ++f) {
-            const uint32_t hi = (uint32_t)(((int64_t)(f + 1) * n + npieces - 1) / npieces);  // columns < hi
+            const uint32_t hi = cut[(size_t)(f + 1) * (phases / fine)];  // columns < hi
             const int64_t end = std::partition_point(ent + pos, ent + len, [&](uint32_t e2) { return (e2 & CBM_ENTRY_INDEX_MASK) < hi; }) - ent;
             auto& list = seg_tasks[(size_t)(f / fine) * (phases + 1) + (fine > 1 ? f % fine : phases)];
             for (int64_t b = pos; b < end; b += split_len) {

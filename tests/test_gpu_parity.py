@@ -164,6 +164,31 @@ def test_split_rows_and_empty_rows(env):
                                 orc.spmm_csr_normalized(rowptr, colidx, Xg)) <= TOL
 
 
+def test_split_rows_with_popular_columns_clustered(env):
+    """Long rows whose entries crowd into the low end of the column range (popular columns next to each other, as in a
+    graph that was not renumbered): the per-XCD column ranges are cut by entry count, some of them only a few columns
+    wide, others empty of a given row; products against the oracle, rows of 1,024 entries and more cut into phases too."""
+    torch, cbm = env
+    rng = np.random.default_rng(11)
+    n = 16000
+    p = 1.0 / (np.arange(n) + 20.0) ** 1.2
+    p /= p.sum()
+    rows = [sorted(rng.choice(n, size=int(s), replace=False, p=p).tolist()) for s in rng.integers(130, 1500, size=300)]
+    rows += [sorted(rng.choice(n, size=int(s), replace=False).tolist()) for s in rng.integers(0, 30, size=n - len(rows))]
+    rowptr, colidx = _csr(rows)
+    for k in (16, 128, 200):
+        X = wl.integer_features(n, k, 3)
+        h = cbm.cbm_build(n, n, rowptr, colidx, max_depth=16)
+        assert cbm.cbm_stats(h)["num_split_rows"] >= 250
+        assert np.array_equal(_run(env, "cbm_spmm", h, X, n).astype(np.float64), orc.spmm_csr(rowptr, colidx, X))
+        cbm.cbm_free(h)
+        Xg = wl.gaussian_features(n, k, 3)
+        h = cbm.cbm_build(n, n, rowptr, colidx, add_self_loops=True)
+        assert row_scaled_error(_run(env, "cbm_spmm_normalized", h, Xg, n),
+                                orc.spmm_csr_normalized(rowptr, colidx, Xg)) <= TOL
+        cbm.cbm_free(h)
+
+
 @pytest.mark.parametrize("name", wl.CONFIGS)
 @pytest.mark.parametrize("k", [3, 64, 128, 500])
 def test_mean_and_gin_aggregators(env, graphs, name, k):
