@@ -1155,7 +1155,7 @@ cbm_status Builder::emit(int32_t nrounds) {
             // on neighbours running side by side instead (collaboration graph with every row stored in full: 0.44 ms in
             // locality order, 0.54 ms longest-first): there the order is by length only in buckets of 32 entries,
             // locality order inside a bucket.  CBM_SHARE_SORT: 0 = locality order, 1 = longest first, n = buckets of n.
-            static const long share_mode = env_clamped("CBM_SHARE_SORT", -1, -1, 1 << 20);
+            const long share_mode = env_clamped("CBM_SHARE_SORT", -1, -1, 1 << 20);
             for (int j = 0; j < CBM_XCD; ++j) {
                 auto b = lt.begin() + (R.xcd_begin[j] - R.task_begin);
                 const long mode = share_mode >= 0 ? share_mode : (R.xcd_count[j] <= kShareSortItems ? 1 : kShareBucket);

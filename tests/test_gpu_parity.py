@@ -523,6 +523,30 @@ def test_bundled_rounds_give_the_same_products(env, graphs, name, monkeypatch):
     assert np.array_equal(Y1, Y2)
 
 
+@pytest.mark.parametrize("name", ["protein", "collaboration"])
+def test_order_inside_xcd_shares_does_not_change_the_product(env, graphs, name, monkeypatch):
+    """Rounds scheduled by locality hand every XCD a share of the work items; the order inside a share (breadth-first,
+    longest first, by length in buckets) is a scheduling choice: every row is still summed in the same order, so the
+    products are the same bit for bit, and equal to the oracle's."""
+    torch, cbm = env
+    g = graphs[name]
+    X = wl.gaussian_features(g.n, 128, g.meta["seed"])
+    ref = orc.spmm_csr_normalized(g.rowptr, g.colidx, X)
+    outs = []
+    for mode in ("0", "1", "7", None):
+        if mode is None:
+            monkeypatch.delenv("CBM_SHARE_SORT", raising=False)
+        else:
+            monkeypatch.setenv("CBM_SHARE_SORT", mode)
+        monkeypatch.setenv("CBM_LOCALITY_MIN", "1")     # every round of the reduced graphs goes by locality
+        h = cbm.cbm_build(g.n, g.n, g.rowptr, g.colidx, add_self_loops=True, alpha=1, max_depth=16)
+        monkeypatch.delenv("CBM_LOCALITY_MIN")
+        outs.append(_run(env, "cbm_spmm_normalized", h, X, g.n))
+        assert row_scaled_error(outs[-1], ref) <= TOL
+        cbm.cbm_free(h)
+    assert all(np.array_equal(outs[0], o) for o in outs[1:])
+
+
 def test_reserve_sizes_the_split_row_scratch_before_capture(env):
     # cbm_reserve instead of a first eager product: a handle WITH split rows is captured at once, and the replay is exact
     torch, cbm = env
