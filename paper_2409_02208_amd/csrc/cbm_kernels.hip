@@ -293,19 +293,25 @@ __global__ __launch_bounds__(256, level_min_waves(RAGGED, LANES, MODE, UMAX)) vo
 // items that start together then move through X together.  The sweep itself is a plain loop: no markers inside it.
 constexpr int bundle_min_waves(bool ragged, int lanes, int mode, int umax) { return umax >= 8 ? (ragged ? 3 : 4) : 6; }
 
-template <bool RAGGED, int LANES, int MODE, int UMAX>
+// WIDE: a work item is shared by two neighbouring groups of the wave, which take its deltas in turn (even places, odd
+// places) and add their partial sums across the groups at the end.  The item's gathers are the same, its chain of
+// dependent batches half as long, and a wave holds half as many work items of unequal length.
+template <bool RAGGED, int LANES, int MODE, int UMAX, bool WIDE>
 __global__ __launch_bounds__(256, bundle_min_waves(RAGGED, LANES, MODE, UMAX)) void cbm_bundle_kernel(
     const CbmTask* __restrict__ tasks, int64_t ntasks, const CbmSegMap map, const uint32_t* __restrict__ stream,
     const float* __restrict__ X, int64_t ldx, float* Y, int64_t ldy, const float* __restrict__ ws, const float* __restrict__ rw,
     float self_w, int k) {
     using M = Mode<MODE>;
-    constexpr int G = 64 / LANES;
-    constexpr int U = LANES < UMAX ? LANES : UMAX;
-    constexpr int BPC = LANES / U;
+    constexpr int S = WIDE ? 2 : 1;               // groups per work item
+    constexpr int G = 64 / LANES / S;             // work items per wave
+    static_assert(G >= 1, "a wide work item needs two groups in a wave");
+    constexpr int U = LANES / S < UMAX ? LANES / S : UMAX;  // rows a group loads per batch
+    constexpr int BPC = LANES / (U * S);          // batches per chunk of LANES entries
     constexpr int R = CBM_BUNDLE_ROWS;
     static_assert(R == 4, "the choice among the partial sums below is written for four rows");
     const int lane = threadIdx.x & 63;
-    const int sub = lane / LANES;
+    const int sub = lane / LANES / S;             // the work item's place in the wave
+    const int half = WIDE ? (lane / LANES) & 1 : 0;  // which of its two groups
     const int sl = lane % LANES;
     int64_t t;
     if (map.use) {
@@ -360,8 +366,8 @@ __global__ __launch_bounds__(256, bundle_min_waves(RAGGED, LANES, MODE, UMAX)) v
         Vec4 x[U];
         uint32_t e[U];
     };
-    const int nb = (int)((len + U - 1) / U);
-    auto fetch = [&](Batch& S, int b) {
+    const int nb = (int)((len + U * S - 1) / (U * S));  // a batch = U entries for every group of the item
+    auto fetch = [&](Batch& Bt, int b) {
         if (b > 0 && b % BPC == 0) {
             const int chunk = b / BPC;
             e0 = e1;
@@ -372,28 +378,28 @@ __global__ __launch_bounds__(256, bundle_min_waves(RAGGED, LANES, MODE, UMAX)) v
             w1 = load_w(e1, chunk + 1);
             cur = chunk;
         }
-        const int off = (b % BPC) * U;
+        const int off = (b % BPC) * U * S + half;  // this group's entries of the batch: every S-th from here
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            S.e[u] = (uint32_t)__shfl((int)e0, off + u, LANES);
-            if ((uint32_t)(b * U + u) < len && colok) {
-                S.x[u] = ld_row<RAGGED, LANES>(X + (int64_t)(S.e[u] & CBM_BUNDLE_INDEX_MASK) * ldx, c0, k);
+            Bt.e[u] = (uint32_t)__shfl((int)e0, off + u * S, LANES);
+            if ((uint32_t)(b * U * S + u * S + half) < len && colok) {
+                Bt.x[u] = ld_row<RAGGED, LANES>(X + (int64_t)(Bt.e[u] & CBM_BUNDLE_INDEX_MASK) * ldx, c0, k);
             } else {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) S.x[u].v[c] = 0.0f;
+                for (int c = 0; c < 4; ++c) Bt.x[u].v[c] = 0.0f;
             }
         }
     };
-    auto consume = [&](const Batch& S, int b) {
+    auto consume = [&](const Batch& Bt, int b) {
         const float wsrc = (b / BPC == cur) ? w0 : wprev;
-        const int off = (b % BPC) * U;
+        const int off = (b % BPC) * U * S + half;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const float w = __shfl(wsrc, off + u, LANES);  // (0 past the end of the deltas, where the row is zero too)
-            const uint32_t slot = (S.e[u] >> CBM_BUNDLE_SLOT_SHIFT) & (uint32_t)(R - 1);  // the same for the whole group
+            const float w = __shfl(wsrc, off + u * S, LANES);  // (0 past the end of the deltas, where the row is zero too)
+            const uint32_t slot = (Bt.e[u] >> CBM_BUNDLE_SLOT_SHIFT) & (uint32_t)(R - 1);  // the same for the whole group
             auto add = [&](Vec4& a) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) a.v[c] = fmaf(w, S.x[u].v[c], a.v[c]);
+                for (int c = 0; c < 4; ++c) a.v[c] = fmaf(w, Bt.x[u].v[c], a.v[c]);
             };
             if (slot & 2u) { if (slot & 1u) add(acc[3]); else add(acc[2]); }
             else { if (slot & 1u) add(acc[1]); else add(acc[0]); }
@@ -407,7 +413,14 @@ __global__ __launch_bounds__(256, bundle_min_waves(RAGGED, LANES, MODE, UMAX)) v
         if (b + 2 < nb) fetch(A, b + 2);
         if (b + 1 < nb) consume(B, b + 1);
     }
-    // the rows of the path, in order: running sum, then the store its marker asks for
+    if (WIDE) {  // the other group's share of every row's deltas
+#pragma unroll
+        for (int s2 = 0; s2 < R; ++s2)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[s2].v[c] += __shfl_xor(acc[s2].v[c], LANES, 64);
+    }
+    // the rows of the path, in order: running sum, then the store its marker asks for (a wide item's two groups hold
+    // the same sums and store alternate rows)
     uint32_t em[R];
     float wm[R];
     Vec4 own[R];
@@ -427,7 +440,8 @@ __global__ __launch_bounds__(256, bundle_min_waves(RAGGED, LANES, MODE, UMAX)) v
         if ((uint32_t)s < nrows) {
             const uint32_t row = em[s] & CBM_ENTRY_INDEX_MASK;
             if (!M::wcol && M::wrow) wm[s] = rw[row];
-            if (M::self && !(em[s] & CBM_ENTRY_INTERNAL) && colok) own[s] = ld_row<RAGGED, LANES>(X + (int64_t)row * ldx, c0, k);
+            if (M::self && !(em[s] & CBM_ENTRY_INTERNAL) && colok && (s & (S - 1)) == half)
+                own[s] = ld_row<RAGGED, LANES>(X + (int64_t)row * ldx, c0, k);
         }
     }
 #pragma unroll
@@ -435,7 +449,7 @@ __global__ __launch_bounds__(256, bundle_min_waves(RAGGED, LANES, MODE, UMAX)) v
         if ((uint32_t)s < nrows) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) run.v[c] += acc[s].v[c];
-            if (colok)
+            if (colok && (s & (S - 1)) == half)
                 store_row<RAGGED, LANES, MODE>(Y + (int64_t)(em[s] & CBM_ENTRY_INDEX_MASK) * ldy, c0, k, run,
                                                !(em[s] & CBM_ENTRY_INTERNAL), wm[s], own[s], self_w);
         }
@@ -535,9 +549,12 @@ struct LaunchCtx {
     float self_w;     // MODE 4
 };
 
-template <bool RAGGED, int LANES, int MODE, int UMAX>
-void launch_bundles(const LaunchCtx& c, const CbmLevel& L) {
-    constexpr int G = 64 / LANES;
+// launches of up to this many waves (counted with one group per work item) share every work item between two groups
+constexpr int64_t kWideMaxWavesDefault = 32768;
+
+template <bool RAGGED, int LANES, int MODE, int UMAX, bool WIDE>
+void launch_bundles_as(const LaunchCtx& c, const CbmLevel& L) {
+    constexpr int G = 64 / LANES / (WIDE ? 2 : 1);
     const int ychunks = (c.k + LANES * 4 - 1) / (LANES * 4);
     CbmSegMap map{};
     if (L.by_xcd) {
@@ -549,13 +566,28 @@ void launch_bundles(const LaunchCtx& c, const CbmLevel& L) {
         }
         map.use = 1;
         dim3 grid((unsigned)(CBM_XCD * ((most + 4 * G - 1) / (4 * G))), (unsigned)ychunks);
-        hipLaunchKernelGGL((cbm_bundle_kernel<RAGGED, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream, c.h->d_tasks,
+        hipLaunchKernelGGL((cbm_bundle_kernel<RAGGED, LANES, MODE, UMAX, WIDE>), grid, dim3(256), 0, c.stream, c.h->d_tasks,
                            (int64_t)c.h->tasks.size(), map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.ws, c.rw, c.self_w, c.k);
         return;
     }
     dim3 grid((unsigned)((L.task_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
-    hipLaunchKernelGGL((cbm_bundle_kernel<RAGGED, LANES, MODE, UMAX>), grid, dim3(256), 0, c.stream, c.h->d_tasks + L.task_begin,
+    hipLaunchKernelGGL((cbm_bundle_kernel<RAGGED, LANES, MODE, UMAX, WIDE>), grid, dim3(256), 0, c.stream, c.h->d_tasks + L.task_begin,
                        L.task_count, map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.ws, c.rw, c.self_w, c.k);
+}
+
+template <bool RAGGED, int LANES, int MODE, int UMAX>
+void launch_bundles(const LaunchCtx& c, const CbmLevel& L) {
+    // Narrow feature matrices only: with four or eight work items in a wave (k <= 64) halving that number is a gain
+    // (protein recipe, k = 64: 0.43 -> 0.34 ms); with two (k = 128, or 256 in chunks of 128) it is a loss (0.80 -> 0.94 ms).
+    if constexpr (LANES <= 16 && UMAX >= 8) {
+        static const int64_t wide_max = [] {
+            const char* e = std::getenv("CBM_WIDE_MAX_WAVES");
+            return e ? std::atoll(e) : kWideMaxWavesDefault;
+        }();
+        const int64_t ychunks = (c.k + LANES * 4 - 1) / (LANES * 4);
+        if (L.task_count / (64 / LANES) * ychunks <= wide_max) return launch_bundles_as<RAGGED, LANES, MODE, UMAX, true>(c, L);
+    }
+    launch_bundles_as<RAGGED, LANES, MODE, UMAX, false>(c, L);
 }
 
 template <bool RAGGED, int LANES, int MODE, int UMAX>
