@@ -291,27 +291,30 @@ __global__ __launch_bounds__(256, level_min_waves(RAGGED, LANES, MODE, UMAX)) vo
 // ascending sweep, each tagged with the row it belongs to; the group keeps one partial sum per row and, when the deltas
 // are done, forms the running sums and stores the rows (the path's markers follow its deltas in the stream).  Work
 // items that start together then move through X together.  The sweep itself is a plain loop: no markers inside it.
-constexpr int bundle_min_waves(bool ragged, int lanes, int mode, int umax) { return umax >= 8 ? (ragged ? 3 : 4) : 6; }
+// (waves per SIMD the register allocation is held to: the variants that would spill at four get three)
+constexpr int bundle_min_waves(bool ragged, int lanes, int mode, int umax, int split) {
+    return umax >= 8 ? (ragged || (lanes <= 16 && split == 1) ? 3 : 4) : 6;
+}
 
-// WIDE: a work item is shared by two neighbouring groups of the wave, which take its deltas in turn (even places, odd
-// places) and add their partial sums across the groups at the end.  The item's gathers are the same, its chain of
-// dependent batches half as long, and a wave holds half as many work items of unequal length.
-template <bool RAGGED, int LANES, int MODE, int UMAX, bool WIDE>
-__global__ __launch_bounds__(256, bundle_min_waves(RAGGED, LANES, MODE, UMAX)) void cbm_bundle_kernel(
+// SPLIT = 2 or 4: a work item is shared by that many neighbouring groups of the wave, which take its deltas in turn
+// (every SPLIT-th place) and add their partial sums across the groups at the end.  The item's gathers are the same, its
+// chain of dependent batches 1/SPLIT as long, and a wave holds 1/SPLIT as many work items of unequal length.
+template <bool RAGGED, int LANES, int MODE, int UMAX, int SPLIT>
+__global__ __launch_bounds__(256, bundle_min_waves(RAGGED, LANES, MODE, UMAX, SPLIT)) void cbm_bundle_kernel(
     const CbmTask* __restrict__ tasks, int64_t ntasks, const CbmSegMap map, const uint32_t* __restrict__ stream,
     const float* __restrict__ X, int64_t ldx, float* Y, int64_t ldy, const float* __restrict__ ws, const float* __restrict__ rw,
     float self_w, int k) {
     using M = Mode<MODE>;
-    constexpr int S = WIDE ? 2 : 1;               // groups per work item
+    constexpr int S = SPLIT;                      // groups per work item
     constexpr int G = 64 / LANES / S;             // work items per wave
-    static_assert(G >= 1, "a wide work item needs two groups in a wave");
+    static_assert(G >= 1 && (S == 1 || S == 2 || S == 4), "the groups of a shared work item lie in one wave");
     constexpr int U = LANES / S < UMAX ? LANES / S : UMAX;  // rows a group loads per batch
     constexpr int BPC = LANES / (U * S);          // batches per chunk of LANES entries
     constexpr int R = CBM_BUNDLE_ROWS;
     static_assert(R == 4, "the choice among the partial sums below is written for four rows");
     const int lane = threadIdx.x & 63;
     const int sub = lane / LANES / S;             // the work item's place in the wave
-    const int half = WIDE ? (lane / LANES) & 1 : 0;  // which of its two groups
+    const int half = S > 1 ? (lane / LANES) & (S - 1) : 0;  // which of the item's groups
     const int sl = lane % LANES;
     int64_t t;
     if (map.use) {
@@ -413,11 +416,14 @@ __global__ __launch_bounds__(256, bundle_min_waves(RAGGED, LANES, MODE, UMAX)) v
         if (b + 2 < nb) fetch(A, b + 2);
         if (b + 1 < nb) consume(B, b + 1);
     }
-    if (WIDE) {  // the other group's share of every row's deltas
+    if (S > 1) {  // the other groups' shares of every row's deltas (the same additions in every group: equal sums)
 #pragma unroll
         for (int s2 = 0; s2 < R; ++s2)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) acc[s2].v[c] += __shfl_xor(acc[s2].v[c], LANES, 64);
+            for (int c = 0; c < 4; ++c) {
+                acc[s2].v[c] += __shfl_xor(acc[s2].v[c], LANES, 64);
+                if (S > 2) acc[s2].v[c] += __shfl_xor(acc[s2].v[c], 2 * LANES, 64);
+            }
     }
     // the rows of the path, in order: running sum, then the store its marker asks for (a wide item's two groups hold
     // the same sums and store alternate rows)
@@ -549,12 +555,12 @@ struct LaunchCtx {
     float self_w;     // MODE 4
 };
 
-// launches of up to this many waves (counted with one group per work item) share every work item between two groups
+// launches of up to this many waves (counted with one group per work item) share every work item among four groups
 constexpr int64_t kWideMaxWavesDefault = 32768;
 
-template <bool RAGGED, int LANES, int MODE, int UMAX, bool WIDE>
+template <bool RAGGED, int LANES, int MODE, int UMAX, int SPLIT>
 void launch_bundles_as(const LaunchCtx& c, const CbmLevel& L) {
-    constexpr int G = 64 / LANES / (WIDE ? 2 : 1);
+    constexpr int G = 64 / LANES / SPLIT;
     const int ychunks = (c.k + LANES * 4 - 1) / (LANES * 4);
     CbmSegMap map{};
     if (L.by_xcd) {
@@ -566,28 +572,31 @@ void launch_bundles_as(const LaunchCtx& c, const CbmLevel& L) {
         }
         map.use = 1;
         dim3 grid((unsigned)(CBM_XCD * ((most + 4 * G - 1) / (4 * G))), (unsigned)ychunks);
-        hipLaunchKernelGGL((cbm_bundle_kernel<RAGGED, LANES, MODE, UMAX, WIDE>), grid, dim3(256), 0, c.stream, c.h->d_tasks,
+        hipLaunchKernelGGL((cbm_bundle_kernel<RAGGED, LANES, MODE, UMAX, SPLIT>), grid, dim3(256), 0, c.stream, c.h->d_tasks,
                            (int64_t)c.h->tasks.size(), map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.ws, c.rw, c.self_w, c.k);
         return;
     }
     dim3 grid((unsigned)((L.task_count + 4 * G - 1) / (4 * G)), (unsigned)ychunks);
-    hipLaunchKernelGGL((cbm_bundle_kernel<RAGGED, LANES, MODE, UMAX, WIDE>), grid, dim3(256), 0, c.stream, c.h->d_tasks + L.task_begin,
+    hipLaunchKernelGGL((cbm_bundle_kernel<RAGGED, LANES, MODE, UMAX, SPLIT>), grid, dim3(256), 0, c.stream, c.h->d_tasks + L.task_begin,
                        L.task_count, map, c.h->d_stream, c.X, c.ldx, c.Y, c.ldy, c.ws, c.rw, c.self_w, c.k);
 }
 
 template <bool RAGGED, int LANES, int MODE, int UMAX>
 void launch_bundles(const LaunchCtx& c, const CbmLevel& L) {
-    // Narrow feature matrices only: with four or eight work items in a wave (k <= 64) halving that number is a gain
-    // (protein recipe, k = 64: 0.43 -> 0.34 ms); with two (k = 128, or 256 in chunks of 128) it is a loss (0.80 -> 0.94 ms).
+    // Narrow feature matrices only (k <= 64: four or eight work items in a wave): the rounds of a tree are then short of
+    // work and last as long as their longest item's chain of dependent batches, whatever k is (protein recipe: 0.43-0.47 ms
+    // for every k from 8 to 64).  Four groups per item: 0.32 ms at k = 64, 0.28 ms at k <= 32.  With two work items in a
+    // wave to begin with (k = 128, or 256 in chunks of 128) the rounds are bound by lines in flight and sharing items out
+    // is a loss (0.80 -> 0.94 ms with two groups per item).
     if constexpr (LANES <= 16 && UMAX >= 8) {
         static const int64_t wide_max = [] {
             const char* e = std::getenv("CBM_WIDE_MAX_WAVES");
             return e ? std::atoll(e) : kWideMaxWavesDefault;
         }();
         const int64_t ychunks = (c.k + LANES * 4 - 1) / (LANES * 4);
-        if (L.task_count / (64 / LANES) * ychunks <= wide_max) return launch_bundles_as<RAGGED, LANES, MODE, UMAX, true>(c, L);
+        if (L.task_count / (64 / LANES) * ychunks <= wide_max) return launch_bundles_as<RAGGED, LANES, MODE, UMAX, 4>(c, L);
     }
-    launch_bundles_as<RAGGED, LANES, MODE, UMAX, false>(c, L);
+    launch_bundles_as<RAGGED, LANES, MODE, UMAX, 1>(c, L);
 }
 
 template <bool RAGGED, int LANES, int MODE, int UMAX>
