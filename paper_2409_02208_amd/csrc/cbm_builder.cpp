@@ -32,6 +32,7 @@ constexpr double kLocalityEntries = 230.0;   // such a round's bandwidth grows b
 constexpr int64_t kBundleMinEntries = 96;   // mean entries per work item from which a round's paths are bundled
 constexpr int64_t kShareSortItems = 8192;   // work items in an XCD's share of a round up to which they run strictly longest first
 constexpr long kShareBucket = 32;           // ... beyond that: by length in buckets of this many entries, locality order inside
+constexpr int64_t kLongSingleRow = 64;      // mean entries of a round of single rows from which the sweep kernel may take it (narrow X)
 constexpr int64_t kBundleMinItems = 256;    // ... and the work items it must have: a round of a few long paths gains nothing from sweeps in step
 constexpr int64_t kDeviceSearchMinRows = 65536;  // from here on a handle bound for a GPU searches its candidates there
 constexpr int64_t kSampleMinRows = 65536;  // automatic mode samples the compressibility of matrices this large first
@@ -1013,6 +1014,8 @@ cbm_status Builder::emit(int32_t nrounds) {
         if (verbose)
             std::fprintf(stderr, "[cbm_build] round %d: %zu work items, %.1f entries each, at most %d rows in a path\n", r, rtasks[r].size(),
                          rtasks[r].empty() ? 0.0 : (double)ent / (double)rtasks[r].size(), (int)most);
+        // (a round of long single rows has the same entries in either layout: the launch picks the kernel by the width of X)
+        h->levels[r - 1].long_single_rows = most == 1 && !rtasks[r].empty() && ent >= kLongSingleRow * (int64_t)rtasks[r].size();
         if (most > 1 && most <= CBM_BUNDLE_ROWS && ent >= bundle_min * (int64_t)rtasks[r].size()) {
             round_bundled[r] = 1;
             h->levels[r - 1].bundled = true;

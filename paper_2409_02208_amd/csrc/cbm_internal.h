@@ -46,6 +46,8 @@ struct CbmLevel {
     int64_t comb_segments = 0;                     // scratch rows read by the combine launch
     int64_t comb_parent_reads = 0;
     bool bundled = false;                          // the round's paths are emitted as bundles (see CBM_BUNDLE_SLOT_SHIFT)
+    bool long_single_rows = false;                 // every path is one row (deltas, then its marker: the same entries in either
+                                                   // layout), long on average, columns below 2^26: either kernel can run the round
     // work items in locality order, cut into one contiguous block per XCD (absolute indices into tasks[])
     bool by_xcd = false;
     int64_t xcd_begin[CBM_XCD] = {}, xcd_count[CBM_XCD] = {};

@@ -558,6 +558,14 @@ struct LaunchCtx {
 // launches of up to this many waves (counted with one group per work item) share every work item among four groups
 constexpr int64_t kWideMaxWavesDefault = 32768;
 
+inline int64_t wide_max_waves() {
+    static const int64_t v = [] {
+        const char* e = std::getenv("CBM_WIDE_MAX_WAVES");
+        return e ? std::atoll(e) : kWideMaxWavesDefault;
+    }();
+    return v;
+}
+
 template <bool RAGGED, int LANES, int MODE, int UMAX, int SPLIT>
 void launch_bundles_as(const LaunchCtx& c, const CbmLevel& L) {
     constexpr int G = 64 / LANES / SPLIT;
@@ -589,12 +597,8 @@ void launch_bundles(const LaunchCtx& c, const CbmLevel& L) {
     // wave to begin with (k = 128, or 256 in chunks of 128) the rounds are bound by lines in flight and sharing items out
     // is a loss (0.80 -> 0.94 ms with two groups per item).
     if constexpr (LANES <= 16 && UMAX >= 8) {
-        static const int64_t wide_max = [] {
-            const char* e = std::getenv("CBM_WIDE_MAX_WAVES");
-            return e ? std::atoll(e) : kWideMaxWavesDefault;
-        }();
         const int64_t ychunks = (c.k + LANES * 4 - 1) / (LANES * 4);
-        if (L.task_count / (64 / LANES) * ychunks <= wide_max) return launch_bundles_as<RAGGED, LANES, MODE, UMAX, 4>(c, L);
+        if (L.task_count / (64 / LANES) * ychunks <= wide_max_waves()) return launch_bundles_as<RAGGED, LANES, MODE, UMAX, 4>(c, L);
     }
     launch_bundles_as<RAGGED, LANES, MODE, UMAX, 1>(c, L);
 }
@@ -606,6 +610,14 @@ void launch_level(const LaunchCtx& c, const CbmLevel& L) {
     CbmSegMap map{};
     if (L.task_count <= 0) return;
     if (L.bundled) return launch_bundles<RAGGED, LANES, MODE, UMAX>(c, L);
+    if constexpr (LANES <= 16 && UMAX >= 8) {
+        // narrow X, a round of long single rows (the roots of a tree): the sweep kernel shares each row among four
+        // groups of the wave; the kernel below would walk it with one (protein recipe, k = 64: that round 0.077 ms, the product
+        // 0.317 -> 0.288 ms)
+        const int64_t ychunks2 = (c.k + LANES * 4 - 1) / (LANES * 4);
+        if (L.long_single_rows && L.task_count / (64 / LANES) * ychunks2 <= wide_max_waves())
+            return launch_bundles_as<RAGGED, LANES, MODE, UMAX, 4>(c, L);
+    }
     if (L.by_xcd) {  // one block of the (locality-ordered) work items per XCD
         int64_t most = 0;
         for (int j = 0; j < CBM_XCD; ++j) {
