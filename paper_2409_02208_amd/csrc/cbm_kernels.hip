@@ -558,12 +558,9 @@ struct LaunchCtx {
 // launches of up to this many waves (counted with one group per work item) share every work item among four groups
 constexpr int64_t kWideMaxWavesDefault = 32768;
 
-inline int64_t wide_max_waves() {
-    static const int64_t v = [] {
-        const char* e = std::getenv("CBM_WIDE_MAX_WAVES");
-        return e ? std::atoll(e) : kWideMaxWavesDefault;
-    }();
-    return v;
+inline int64_t wide_max_waves() {  // (read at every launch, so that a test can run both forms in one process)
+    const char* e = std::getenv("CBM_WIDE_MAX_WAVES");
+    return e ? std::atoll(e) : kWideMaxWavesDefault;
 }
 
 template <bool RAGGED, int LANES, int MODE, int UMAX, int SPLIT>

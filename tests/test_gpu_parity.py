@@ -500,6 +500,11 @@ def test_bundled_rounds_give_the_same_products(env, graphs, name, monkeypatch):
         X = wl.gaussian_features(g.n, k, g.meta["seed"])
         ref = orc.spmm_csr_normalized(g.rowptr, g.colidx, X)
         assert row_scaled_error(_run(env, "cbm_spmm_normalized", h, X, g.n), ref) <= TOL
+        if k <= 64:   # narrow X shares a work item among four groups of a wave; the one-group form of the same kernel too
+            monkeypatch.setenv("CBM_WIDE_MAX_WAVES", "0")
+            assert row_scaled_error(_run(env, "cbm_spmm_normalized", h, X, g.n), ref) <= TOL
+            assert np.array_equal(_run(env, "cbm_spmm", hp, Xi, g.n).astype(np.float64), orc.spmm_csr(g.rowptr, g.colidx, Xi))
+            monkeypatch.delenv("CBM_WIDE_MAX_WAVES")
         assert row_scaled_error(_run(env, "cbm_spmm_normalized_relu", h, X, g.n), np.maximum(ref, 0.0), scale_from=ref) <= TOL
         mean = (orc.spmm_csr(g.rowptr, g.colidx, X) + X.astype(np.float64)) / d[:, None]
         assert row_scaled_error(_run(env, "cbm_spmm_mean", h, X, g.n), mean) <= TOL
